@@ -1,0 +1,181 @@
+"""Seeded synthetic inputs shaped like MMDiT joint-attention layers, and per-head plans.
+
+This module only *draws inputs*: it holds none of the operator's arithmetic and is
+the one piece both the GPU library's callers and the CPU oracle's callers share.
+
+The real workloads of the paper (Sec. 4.1: SD3 / FLUX.1-dev activations on MS-COCO
+captions; Sec. 4.5: 4096+512 and 16384+512 tokens) are not available offline; the
+generators below take only their shapes and the structure Sec. 3.1 describes: an
+image-image block that is local around the diagonal, heads that differ from global
+to very local, and an arbitrary text block.
+
+Layout everywhere: [B, H, N, D], N = n_text + n_img, text tokens first, image token
+(y, x) of a G x G grid at index n_text + y*G + x.
+"""
+from dataclasses import dataclass, field
+import math
+
+import numpy as np
+import torch
+
+FULL, ARROW, CACHE = 0, 1, 2
+
+
+@dataclass
+class Workload:
+    name: str
+    B: int
+    H: int
+    D: int
+    n_text: int
+    n_img: int
+    head_plan: np.ndarray
+    window: np.ndarray
+    seed: int
+    positional: bool = True
+    notes: str = ""
+    extra: dict = field(default_factory=dict)
+
+    @property
+    def N(self) -> int:
+        return self.n_text + self.n_img
+
+    @property
+    def scale(self) -> float:
+        return 1.0 / math.sqrt(self.D)
+
+
+def positional_term(n_img: int, D: int, amplitude: float = 1.5) -> np.ndarray:
+    """Smooth 2-D sinusoidal term [n_img, D] shared by every head and batch entry.
+
+    Frequencies run from a period of 2 tokens to a period of 2G tokens, alternating
+    sin/cos of the row and of the column, so that q.k between two image tokens peaks
+    when they are close on the grid.
+    """
+    G = int(round(math.sqrt(n_img)))
+    assert G * G == n_img and D % 4 == 0
+    nk = D // 4
+    kk = np.arange(nk, dtype=np.float64)
+    omega = np.pi / np.power(float(G), kk / max(nk - 1, 1))
+    y = np.repeat(np.arange(G, dtype=np.float64), G)[:, None]
+    x = np.tile(np.arange(G, dtype=np.float64), G)[:, None]
+    pos = np.empty((n_img, D), dtype=np.float64)
+    pos[:, 0::4] = np.sin(omega * y)
+    pos[:, 1::4] = np.cos(omega * y)
+    pos[:, 2::4] = np.sin(omega * x)
+    pos[:, 3::4] = np.cos(omega * x)
+    return (amplitude * pos).astype(np.float32)
+
+
+def _normal(seed, stream, shape) -> np.ndarray:
+    # Philox is counter based: (seed, stream) names an independent sequence.
+    g = np.random.Generator(np.random.Philox(key=[int(seed), int(stream)]))
+    return g.standard_normal(size=shape, dtype=np.float32)
+
+
+def make_qkv(wl: Workload, step: int = 0, dtype=torch.bfloat16):
+    """Q, K, V = N(0,1) (+ the positional term on image tokens), rounded to `dtype`."""
+    shape = (wl.B, wl.H, wl.N, wl.D)
+    outs = []
+    pos = positional_term(wl.n_img, wl.D) if (wl.positional and wl.n_img > 0) else None
+    for t in range(3):
+        a = _normal(wl.seed, 16 * step + t, shape)
+        if pos is not None:
+            a[:, :, wl.n_text:, :] += pos
+        outs.append(torch.from_numpy(a).to(dtype))
+    return tuple(outs)
+
+
+def make_cache(wl: Workload, step: int = 0, dtype=torch.bfloat16):
+    """A stand-in previous-step output buffer: N(0,1) drawn from its own stream."""
+    a = _normal(wl.seed + 1, 16 * step + 7, (wl.B, wl.H, wl.N, wl.D))
+    return torch.from_numpy(a).to(dtype)
+
+
+def shuffled_plan(H, counts, seed):
+    """counts: list of (mode, window, how_many); positions shuffled by `seed`."""
+    modes, wins = [], []
+    for mode, w, c in counts:
+        modes += [mode] * c
+        wins += [w] * c
+    assert len(modes) == H
+    perm = np.random.Generator(np.random.PCG64(seed)).permutation(H)
+    return (np.asarray(modes, dtype=np.int32)[perm].copy(),
+            np.asarray(wins, dtype=np.int32)[perm].copy())
+
+
+def tiny() -> Workload:
+    hp = np.array([FULL, ARROW, ARROW, CACHE], dtype=np.int32)
+    win = np.array([0, 8, 16, 0], dtype=np.int32)
+    return Workload("tiny", 1, 4, 64, 16, 64, hp, win, seed=0, positional=False,
+                    notes="B=1 H=4 D=64 n_text=16 n_img=64 (8x8); plain N(0,1)")
+
+
+def sd3_1k() -> Workload:
+    hp, win = shuffled_plan(24, [(FULL, 0, 8), (ARROW, 256, 3), (ARROW, 512, 3), (ARROW, 1024, 2),
+                                 (CACHE, 0, 8)], seed=2)
+    return Workload("sd3_1k", 2, 24, 64, 333, 4096, hp, win, seed=2,
+                    notes="SD3-medium-like 1024^2 layer, CFG pair")
+
+
+def flux_1k() -> Workload:
+    hp, win = shuffled_plan(24, [(FULL, 0, 6), (ARROW, 128, 3), (ARROW, 256, 3), (ARROW, 512, 3),
+                                 (ARROW, 1024, 3), (CACHE, 0, 6)], seed=3)
+    return Workload("flux_1k", 1, 24, 128, 512, 4096, hp, win, seed=3,
+                    notes="FLUX-like 1024^2 layer")
+
+
+def flux_2k_mixed() -> Workload:
+    # 5 full, 13 arrow (4 x w512, 4 x w1024, 5 x w2048), 6 cache: about 68 % fewer
+    # attention FLOPs than dense, the reduction the paper reports for FLUX at 2K.
+    hp, win = shuffled_plan(24, [(FULL, 0, 5), (ARROW, 512, 4), (ARROW, 1024, 4), (ARROW, 2048, 5),
+                                 (CACHE, 0, 6)], seed=4)
+    return Workload("flux_2k_mixed", 1, 24, 128, 512, 16384, hp, win, seed=4,
+                    notes="FLUX-like 2048^2 layer, mixed plan (~68 % FLOP reduction)")
+
+
+def flux_2k_full() -> Workload:
+    wl = flux_2k_mixed()
+    wl.name = "flux_2k_full"
+    wl.head_plan = np.zeros(24, dtype=np.int32)
+    wl.window = np.zeros(24, dtype=np.int32)
+    wl.notes = "FLUX-like 2048^2 layer, every head full (dense baseline)"
+    return wl
+
+
+def flux_2k_single_mode(mode: int, w: int = 0) -> Workload:
+    wl = flux_2k_mixed()
+    wl.name = f"flux_2k_mode{mode}_w{w}"
+    wl.head_plan = np.full(24, mode, dtype=np.int32)
+    wl.window = np.full(24, w, dtype=np.int32)
+    return wl
+
+
+def schedule_plans(layers: int, steps: int, H: int = 24, seed: int = 5):
+    """Per-(layer, step, head) plan: step 0 all full, cache only after step 0.
+
+    Later steps draw 5 full / 13 arrow (w in {512, 1024, 2048}) / 6 cache per layer,
+    positions and windows seeded by (seed, layer, step).
+    Returns (head_plan[L,T,H], window[L,T,H]) int32.
+    """
+    hp = np.zeros((layers, steps, H), dtype=np.int32)
+    win = np.zeros((layers, steps, H), dtype=np.int32)
+    for l in range(layers):
+        for t in range(1, steps):
+            g = np.random.Generator(np.random.Philox(key=[seed, l * 4096 + t]))
+            modes = np.array([FULL] * 5 + [ARROW] * 13 + [CACHE] * 6, dtype=np.int32)
+            ws = g.choice(np.array([512, 1024, 2048], dtype=np.int32), size=H)
+            perm = g.permutation(H)
+            hp[l, t] = modes[perm]
+            win[l, t] = np.where(hp[l, t] == ARROW, ws, 0)
+    return hp, win
+
+
+CONFIGS = {
+    "tiny": tiny, "sd3_1k": sd3_1k, "flux_1k": flux_1k,
+    "flux_2k_mixed": flux_2k_mixed, "flux_2k_full": flux_2k_full,
+}
+
+
+def config(name: str) -> Workload:
+    return CONFIGS[name]()
