@@ -1,0 +1,154 @@
+/*
+ * difa.h -- C ABI of the head-wise MMDiT joint-attention library for AMD MI355X (gfx950).
+ *
+ * The operator is the fused multi-strategy attention of DiTFastAttnV2, Sec. 3.3: in one
+ * call every head of a layer independently runs
+ *   - full attention                                   (DIFA_HEAD_FULL),
+ *   - arrow attention with its own window, Sec. 3.1    (DIFA_HEAD_ARROW): the language-to-
+ *     anything and visual-to-language quadrants are kept whole and the visual-to-visual
+ *     quadrant keeps the band |i - j| <= w of the flattened image sequence, or
+ *   - output caching, Sec. 3.2                         (DIFA_HEAD_CACHE): attention is skipped
+ *     and the head's output of the previous denoising step is reused
+ *     (Alg. 1: "O[idx] = O_cache[idx]").
+ *
+ * Conventions: N = n_text + n_img tokens, text tokens first ([0, n_text)), image tokens
+ * after them in flattened row-major order.  Tensors are dense [batch, heads, N, head_dim]
+ * (DIFA_LAYOUT_BHND) or [batch, N, heads, head_dim] (DIFA_LAYOUT_BNHD), head_dim contiguous.
+ *
+ * Plain C99: no C++ types, no HIP headers needed by callers.  No entry point throws or
+ * aborts; every failure is a return code and launches nothing.
+ */
+#ifndef DIFA_H
+#define DIFA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct difa_plan difa_plan_t; /* opaque */
+
+typedef enum {
+    DIFA_OK = 0,
+    DIFA_ERR_INVALID_ARG = 1, /* NULL pointer, bad mode/window/size, missing cache        */
+    DIFA_ERR_UNSUPPORTED = 2, /* head_dim, dtype, layout or device the library cannot run */
+    DIFA_ERR_ALLOC = 3,       /* host or device allocation failed                         */
+    DIFA_ERR_HIP = 4          /* a HIP runtime call failed; text in difa_last_error()     */
+} difa_status_t;
+
+enum { DIFA_HEAD_FULL = 0, DIFA_HEAD_ARROW = 1, DIFA_HEAD_CACHE = 2 };
+enum { DIFA_DTYPE_BF16 = 0, DIFA_DTYPE_F32 = 1 }; /* F32 = slow all-fp32 debug path */
+enum { DIFA_LAYOUT_BHND = 0, DIFA_LAYOUT_BNHD = 1 };
+
+/* Static description of a layer's attention call; fixed for the life of a plan object. */
+typedef struct {
+    int32_t batch;         /* B >= 1; the per-head plan is shared by all batch entries      */
+    int32_t heads;         /* H >= 1                                                       */
+    int32_t head_dim;      /* 64 or 128                                                    */
+    int32_t dtype;         /* DIFA_DTYPE_*: element type of q, k, v, out and cache         */
+    int32_t layout;        /* DIFA_LAYOUT_*                                                */
+    int32_t max_tokens;    /* upper bound on n_text + n_img of any later call (>= 1)       */
+    float   softmax_scale; /* 0 selects 1/sqrt(head_dim)                                   */
+    int32_t device;        /* HIP device ordinal                                           */
+    uint32_t flags;        /* reserved, must be 0                                          */
+} difa_plan_desc_t;
+
+/*
+ * Create the per-layer plan object (Sec. 3.3: the operator is driven by a per-head plan;
+ * Sec. 3.4.2: the plan is indexed by timestep, layer and head -- one object serves one layer
+ * shape and is fed that layer's per-step head plan on every call).
+ *   desc      HOST pointer, read during the call only.
+ *   plan_out  HOST pointer; receives the object.  The object owns small device and pinned
+ *             host buffers (compiled work lists), sized from desc->max_tokens.
+ * Errors: INVALID_ARG (NULL, sizes < 1, flags != 0), UNSUPPORTED (head_dim not 64/128,
+ * unknown dtype/layout, device is not gfx950), ALLOC, HIP.  On error *plan_out is NULL.
+ */
+difa_status_t difa_plan_create(const difa_plan_desc_t* desc, difa_plan_t** plan_out);
+
+/*
+ * One fused head-wise joint-attention call (Sec. 3.3; Alg. 1, "HeadwiseAttention(Q,K,V,Plan)"
+ * followed by "O[idx] = O_cache[idx]").
+ *   q, k, v    DEVICE, read-only, shape/layout/dtype of the plan, N = n_text + n_img.
+ *   out        DEVICE, same shape; every row of every head is written.  Must not alias q/k/v.
+ *   cache      DEVICE, same shape: the layer's output of the previous denoising step.  Read
+ *              only for CACHE heads, whose rows are copied bit for bit.  May be NULL iff no
+ *              head is CACHE.  cache == out is allowed (CACHE heads are then left untouched).
+ *   head_plan  HOST, int32[heads], DIFA_HEAD_* per head.
+ *   n_text, n_img  token counts (>= 0, sum in [1, max_tokens]).
+ *   window     HOST, int32[heads], half-width w >= 0 of each ARROW head (an image query i
+ *              sees image keys j with |i - j| <= w); ignored for other heads; may be NULL iff
+ *              no head is ARROW.  w >= n_img - 1 makes the head identical to FULL.
+ *   stream     hipStream_t passed as void*; NULL is the default stream.
+ * The call enqueues work on `stream` and returns without waiting; host arrays may be freed
+ * on return.  Device tensors stay owned by the caller and must stay valid until the stream
+ * has run the work.  Calls on one plan object must not be issued from two threads at once.
+ * Errors: INVALID_ARG, HIP.  On error nothing has been enqueued.
+ */
+difa_status_t difa_joint_attention(difa_plan_t* plan, const void* q, const void* k, const void* v,
+                                   void* out, const void* cache, const int32_t* head_plan,
+                                   int32_t n_text, int32_t n_img, const int32_t* window,
+                                   void* stream);
+
+/* Release the object and its buffers (waits for the device to finish work that uses them).
+ * NULL is a no-op that returns DIFA_OK. */
+difa_status_t difa_plan_destroy(difa_plan_t* plan);
+
+/* Static text for a status code. */
+const char* difa_status_string(difa_status_t status);
+
+/* Text of the last failure on this plan (owned by the plan, valid until its next call);
+ * with plan == NULL, the text of the last failed difa_plan_create in this thread. */
+const char* difa_last_error(const difa_plan_t* plan);
+
+/* ------------------------------------------------------------------ host-side work list
+ * Sec. 4.5 names the per-thread-block determination of the arrow pattern as the overhead
+ * that shows at high sparsity.  Here that determination is done once on the host: the head
+ * plan is compiled into one record per (batch entry, computed head, query tile) that lists
+ * the key tiles the tile must visit, so that masked tiles are never loaded and in-tile masks
+ * are applied only where a band edge, the text/image boundary or the sequence end crosses a
+ * tile.  Exposed so that it can be checked without a GPU.
+ */
+typedef struct {
+    int32_t bh;        /* batch * heads + head                                            */
+    int32_t q_tile;    /* query rows [q_tile*bm, min(N, (q_tile+1)*bm)); < 0: padding     */
+    int32_t kv0_end;   /* first key-tile range  [0, kv0_end)          (text keys, or all) */
+    int32_t nm0_end;   /*   tiles [0, nm0_end) of it need no in-tile mask                 */
+    int32_t kv1_begin; /* second key-tile range [kv1_begin, kv1_end)  (band), >= kv0_end  */
+    int32_t kv1_end;
+    int32_t nm1_begin; /*   tiles [nm1_begin, nm1_end) of it need no in-tile mask         */
+    int32_t nm1_end;
+    int32_t window;    /* half-width for an ARROW head, -1 for a FULL head                */
+    int32_t n_tiles;   /* number of key tiles visited (the record's cost)                 */
+} difa_work_item_t;
+
+/* Tile shape (query rows bm, keys bn) the kernels use for a head_dim/dtype; 0 on success. */
+int32_t difa_tile_shape(int32_t head_dim, int32_t dtype, int32_t* bm, int32_t* bn);
+
+/*
+ * Compile a head plan into work items (HOST only, no GPU needed).
+ *   items/capacity  HOST array to fill (may be NULL with capacity 0 to only count).
+ *   n_items_out     number of records the plan needs (written also when capacity is short).
+ *   copy_heads/n_copy_out  optional: int32[heads] receiving the indices of CACHE heads.
+ * Records are ordered most-key-tiles-first.  Returns DIFA_OK, INVALID_ARG (bad mode/window/
+ * sizes) or ALLOC (capacity too small; nothing useful in items).
+ */
+difa_status_t difa_worklist_build(int32_t batch, int32_t heads, const int32_t* head_plan,
+                                  const int32_t* window, int32_t n_text, int32_t n_img,
+                                  int32_t bm, int32_t bn, difa_work_item_t* items,
+                                  int32_t capacity, int32_t* n_items_out, int32_t* copy_heads,
+                                  int32_t* n_copy_out);
+
+/* ------------------------------------------------------------------ measurement hooks
+ * With timing enabled the library brackets its attention kernel (not the cache copy) with
+ * HIP events on the caller's stream; difa_plan_timing_read waits for the last bracket and
+ * returns the accumulated kernel milliseconds and launch count since the last reset.
+ */
+difa_status_t difa_plan_timing_enable(difa_plan_t* plan, int32_t enable);
+difa_status_t difa_plan_timing_read(difa_plan_t* plan, double* attn_ms, double* copy_ms,
+                                    int64_t* launches, int32_t reset);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DIFA_H */

@@ -1,0 +1,157 @@
+"""ctypes binding of libdifa.so: argument marshalling only, same names as include/difa.h.
+
+PyTorch is used for device memory and streams; every step of the operator runs in the HIP
+library.  There is no fallback: if the library is missing, importing this module fails.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libdifa.so")
+
+DIFA_OK, DIFA_ERR_INVALID_ARG, DIFA_ERR_UNSUPPORTED, DIFA_ERR_ALLOC, DIFA_ERR_HIP = range(5)
+DIFA_HEAD_FULL, DIFA_HEAD_ARROW, DIFA_HEAD_CACHE = 0, 1, 2
+DIFA_DTYPE_BF16, DIFA_DTYPE_F32 = 0, 1
+DIFA_LAYOUT_BHND, DIFA_LAYOUT_BNHD = 0, 1
+
+
+class difa_plan_desc_t(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("layout", ctypes.c_int32), ("max_tokens", ctypes.c_int32),
+                ("softmax_scale", ctypes.c_float), ("device", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+
+
+class difa_work_item_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("bh", "q_tile", "kv0_end", "nm0_end", "kv1_begin", "kv1_end", "nm1_begin", "nm1_end",
+                 "window", "n_tiles")]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2503_22796_amd.build` "
+                          "(there is no fallback path)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32, i32p = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)
+    L.difa_plan_create.restype = ctypes.c_int
+    L.difa_plan_create.argtypes = [ctypes.POINTER(difa_plan_desc_t), ctypes.POINTER(vp)]
+    L.difa_joint_attention.restype = ctypes.c_int
+    L.difa_joint_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp]
+    L.difa_plan_destroy.restype = ctypes.c_int
+    L.difa_plan_destroy.argtypes = [vp]
+    L.difa_status_string.restype = ctypes.c_char_p
+    L.difa_status_string.argtypes = [ctypes.c_int]
+    L.difa_last_error.restype = ctypes.c_char_p
+    L.difa_last_error.argtypes = [vp]
+    L.difa_tile_shape.restype = i32
+    L.difa_tile_shape.argtypes = [i32, i32, i32p, i32p]
+    L.difa_worklist_build.restype = ctypes.c_int
+    L.difa_worklist_build.argtypes = [i32, i32, vp, vp, i32, i32, i32, i32, vp, i32, i32p, vp, i32p]
+    L.difa_plan_timing_enable.restype = ctypes.c_int
+    L.difa_plan_timing_enable.argtypes = [vp, i32]
+    L.difa_plan_timing_read.restype = ctypes.c_int
+    L.difa_plan_timing_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                        ctypes.POINTER(ctypes.c_int64), i32]
+    return L
+
+
+lib = _load()
+
+
+class DifaError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__(f"difa status {status} ({lib.difa_status_string(status).decode()}): {text}")
+        self.status = status
+
+
+def difa_status_string(status: int) -> str:
+    return lib.difa_status_string(int(status)).decode()
+
+
+def difa_last_error(plan=None) -> str:
+    return lib.difa_last_error(plan).decode()
+
+
+def difa_tile_shape(head_dim: int, dtype: int = DIFA_DTYPE_BF16):
+    bm, bn = ctypes.c_int32(0), ctypes.c_int32(0)
+    if lib.difa_tile_shape(head_dim, dtype, ctypes.byref(bm), ctypes.byref(bn)) != 0:
+        raise DifaError(DIFA_ERR_UNSUPPORTED, "difa_tile_shape: unsupported head_dim/dtype")
+    return bm.value, bn.value
+
+
+def _i32(a):
+    return None if a is None else np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+def difa_worklist_build(batch, heads, head_plan, window, n_text, n_img, bm, bn):
+    """Returns (status, items as a numpy structured array, CACHE-head indices)."""
+    hp, win = _i32(head_plan), _i32(window)
+    n_items, n_copy = ctypes.c_int32(0), ctypes.c_int32(0)
+    copy_heads = np.zeros(max(int(heads), 1), dtype=np.int32)
+    st = lib.difa_worklist_build(batch, heads, hp.ctypes.data if hp is not None else None,
+                                 win.ctypes.data if win is not None else None, n_text, n_img, bm, bn,
+                                 None, 0, ctypes.byref(n_items), None, ctypes.byref(n_copy))
+    if st != DIFA_OK:
+        return st, None, None
+    items = (difa_work_item_t * max(n_items.value, 1))()
+    st = lib.difa_worklist_build(batch, heads, hp.ctypes.data, win.ctypes.data if win is not None else None,
+                                 n_text, n_img, bm, bn, ctypes.cast(items, ctypes.c_void_p), n_items.value,
+                                 ctypes.byref(n_items), copy_heads.ctypes.data, ctypes.byref(n_copy))
+    arr = np.frombuffer(items, dtype=np.dtype([(n, np.int32) for n, _ in difa_work_item_t._fields_]),
+                        count=n_items.value).copy()
+    return st, arr, copy_heads[:n_copy.value].copy()
+
+
+def difa_plan_create(batch, heads, head_dim, dtype=DIFA_DTYPE_BF16, layout=DIFA_LAYOUT_BHND,
+                     max_tokens=1, softmax_scale=0.0, device=0, flags=0):
+    desc = difa_plan_desc_t(batch, heads, head_dim, dtype, layout, max_tokens, softmax_scale, device, flags)
+    plan = ctypes.c_void_p()
+    st = lib.difa_plan_create(ctypes.byref(desc), ctypes.byref(plan))
+    if st != DIFA_OK:
+        raise DifaError(st, difa_last_error(None))
+    return plan
+
+
+def difa_plan_destroy(plan):
+    st = lib.difa_plan_destroy(plan)
+    if st != DIFA_OK:
+        raise DifaError(st, "difa_plan_destroy")
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def difa_joint_attention(plan, q, k, v, out, cache, head_plan, n_text, n_img, window, stream=None):
+    """q, k, v, out, cache: torch tensors on the plan's device (cache may be None).
+
+    `stream`: a torch.cuda.Stream, a raw hipStream_t integer, or None for torch's current stream.
+    """
+    import torch
+    hp, win = _i32(head_plan), _i32(window)
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device).cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    st = lib.difa_joint_attention(plan, _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(cache),
+                                  hp.ctypes.data if hp is not None else None, int(n_text), int(n_img),
+                                  win.ctypes.data if win is not None else None, ctypes.c_void_p(stream))
+    if st != DIFA_OK:
+        raise DifaError(st, difa_last_error(plan))
+
+
+def difa_plan_timing_enable(plan, enable=True):
+    st = lib.difa_plan_timing_enable(plan, 1 if enable else 0)
+    if st != DIFA_OK:
+        raise DifaError(st, "difa_plan_timing_enable")
+
+
+def difa_plan_timing_read(plan, reset=True):
+    """Returns (attention kernel ms, copy kernel ms, attention launches) accumulated so far."""
+    a, c, n = ctypes.c_double(0), ctypes.c_double(0), ctypes.c_int64(0)
+    st = lib.difa_plan_timing_read(plan, ctypes.byref(a), ctypes.byref(c), ctypes.byref(n), 1 if reset else 0)
+    if st != DIFA_OK:
+        raise DifaError(st, difa_last_error(plan))
+    return a.value, c.value, n.value

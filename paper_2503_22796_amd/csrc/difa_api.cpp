@@ -1,0 +1,359 @@
+// Host side of the C ABI: argument checking, the per-plan memo of compiled work lists, and
+// the launches.  The operator is Sec. 3.3 of the paper (per-head full / arrow / cached
+// output, cached heads filled as in the last statement of Alg. 1).
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <string>
+#include <vector>
+
+#include "difa_internal.h"
+
+namespace {
+
+constexpr int kSlots = 8;  // distinct (head plan, n_text, n_img) work lists kept resident
+
+struct Slot {
+    std::vector<int32_t> key;
+    void* h_buf = nullptr;  // pinned host staging: items, then CACHE-head indices
+    void* d_buf = nullptr;  // device copy
+    int32_t n_items = 0, n_copy = 0;
+    hipEvent_t uploaded = nullptr;  // recorded after the host-to-device copy
+    hipEvent_t last_use = nullptr;  // recorded after the last launch that reads d_buf
+    hipStream_t upload_stream = nullptr;
+    bool valid = false, used = false;
+    uint64_t stamp = 0;
+};
+
+struct TimingPair {
+    hipEvent_t start, stop;
+    int kind;  // 0 attention, 1 copy
+};
+
+}  // namespace
+
+struct difa_plan {
+    difa_plan_desc_t desc;
+    float scale;
+    int32_t bm, bn;
+    int32_t item_capacity;
+    size_t buf_bytes, copy_off;
+    Slot slots[kSlots];
+    uint64_t clock = 0;
+    std::string err;
+    bool timing = false;
+    std::vector<TimingPair> pending, pool;
+    double attn_ms = 0, copy_ms = 0;
+    int64_t launches = 0;
+};
+
+namespace {
+
+thread_local std::string g_create_err;
+
+difa_status_t fail(difa_plan* p, difa_status_t st, const std::string& msg) {
+    if (p) p->err = msg; else g_create_err = msg;
+    return st;
+}
+
+std::string hip_msg(const char* what, hipError_t e) {
+    return std::string(what) + ": " + hipGetErrorString(e);
+}
+
+size_t elem_size(int dtype) { return dtype == DIFA_DTYPE_BF16 ? 2 : 4; }
+
+void free_slot(Slot& s) {
+    if (s.h_buf) (void)hipHostFree(s.h_buf);
+    if (s.d_buf) (void)hipFree(s.d_buf);
+    if (s.uploaded) (void)hipEventDestroy(s.uploaded);
+    if (s.last_use) (void)hipEventDestroy(s.last_use);
+    s = Slot();
+}
+
+// Switches to the plan's device for the scope of a call and back afterwards.
+struct DeviceGuard {
+    int prev = -1;
+    bool switched = false;
+    hipError_t enter(int dev) {
+        hipError_t e = hipGetDevice(&prev);
+        if (e != hipSuccess) return e;
+        if (prev != dev) {
+            e = hipSetDevice(dev);
+            if (e != hipSuccess) return e;
+            switched = true;
+        }
+        return hipSuccess;
+    }
+    ~DeviceGuard() {
+        if (switched) (void)hipSetDevice(prev);
+    }
+};
+
+hipError_t timing_begin(difa_plan* p, hipStream_t stream, int kind, TimingPair* out) {
+    TimingPair tp{};
+    if (!p->pool.empty()) {
+        tp = p->pool.back();
+        p->pool.pop_back();
+    } else {
+        hipError_t e = hipEventCreate(&tp.start);
+        if (e != hipSuccess) return e;
+        e = hipEventCreate(&tp.stop);
+        if (e != hipSuccess) { (void)hipEventDestroy(tp.start); return e; }
+    }
+    tp.kind = kind;
+    *out = tp;
+    return hipEventRecord(tp.start, stream);
+}
+
+hipError_t timing_flush(difa_plan* p) {
+    hipError_t first = hipSuccess;
+    for (TimingPair& tp : p->pending) {
+        hipError_t e = hipEventSynchronize(tp.stop);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, tp.start, tp.stop);
+        if (e == hipSuccess) {
+            if (tp.kind == 0) { p->attn_ms += ms; p->launches += 1; } else p->copy_ms += ms;
+        } else if (first == hipSuccess) {
+            first = e;
+        }
+        p->pool.push_back(tp);
+    }
+    p->pending.clear();
+    return first;
+}
+
+}  // namespace
+
+extern "C" const char* difa_status_string(difa_status_t st) {
+    switch (st) {
+        case DIFA_OK: return "ok";
+        case DIFA_ERR_INVALID_ARG: return "invalid argument";
+        case DIFA_ERR_UNSUPPORTED: return "unsupported configuration";
+        case DIFA_ERR_ALLOC: return "allocation failed";
+        case DIFA_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+extern "C" const char* difa_last_error(const difa_plan_t* plan) {
+    return plan ? plan->err.c_str() : g_create_err.c_str();
+}
+
+extern "C" difa_status_t difa_plan_create(const difa_plan_desc_t* desc, difa_plan_t** plan_out) {
+    if (plan_out) *plan_out = nullptr;
+    if (!desc || !plan_out) return fail(nullptr, DIFA_ERR_INVALID_ARG, "desc and plan_out must not be NULL");
+    if (desc->batch < 1 || desc->heads < 1 || desc->max_tokens < 1 || desc->flags != 0 || desc->device < 0)
+        return fail(nullptr, DIFA_ERR_INVALID_ARG, "batch, heads, max_tokens must be >= 1, device >= 0, flags 0");
+    if (!(desc->softmax_scale >= 0.f) || isinf(desc->softmax_scale))
+        return fail(nullptr, DIFA_ERR_INVALID_ARG, "softmax_scale must be finite and >= 0 (0 = 1/sqrt(head_dim))");
+    if (desc->head_dim != 64 && desc->head_dim != 128)
+        return fail(nullptr, DIFA_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
+    if (desc->dtype != DIFA_DTYPE_BF16 && desc->dtype != DIFA_DTYPE_F32)
+        return fail(nullptr, DIFA_ERR_UNSUPPORTED, "dtype must be DIFA_DTYPE_BF16 or DIFA_DTYPE_F32");
+    if (desc->layout != DIFA_LAYOUT_BHND && desc->layout != DIFA_LAYOUT_BNHD)
+        return fail(nullptr, DIFA_ERR_UNSUPPORTED, "layout must be DIFA_LAYOUT_BHND or DIFA_LAYOUT_BNHD");
+
+    int n_dev = 0;
+    hipError_t e = hipGetDeviceCount(&n_dev);
+    if (e != hipSuccess) return fail(nullptr, DIFA_ERR_HIP, hip_msg("hipGetDeviceCount", e));
+    if (desc->device >= n_dev) return fail(nullptr, DIFA_ERR_INVALID_ARG, "device ordinal out of range");
+    hipDeviceProp_t prop;
+    e = hipGetDeviceProperties(&prop, desc->device);
+    if (e != hipSuccess) return fail(nullptr, DIFA_ERR_HIP, hip_msg("hipGetDeviceProperties", e));
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+        return fail(nullptr, DIFA_ERR_UNSUPPORTED, std::string("device is ") + prop.gcnArchName + ", kernels are built for gfx950 only");
+
+    difa_plan* p = new (std::nothrow) difa_plan();
+    if (!p) return fail(nullptr, DIFA_ERR_ALLOC, "out of host memory");
+    p->desc = *desc;
+    p->scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)desc->head_dim);
+    difa_tile_shape(desc->head_dim, desc->dtype, &p->bm, &p->bn);
+    const int64_t q_tiles = ((int64_t)desc->max_tokens + p->bm - 1) / p->bm;
+    const int64_t cap = (int64_t)desc->batch * desc->heads * q_tiles;
+    if (cap > (int64_t)1 << 26) {
+        delete p;
+        return fail(nullptr, DIFA_ERR_UNSUPPORTED, "batch*heads*query tiles exceeds the work-list limit");
+    }
+    p->item_capacity = (int32_t)cap;
+    p->copy_off = (size_t)cap * sizeof(difa_work_item_t);
+    p->buf_bytes = p->copy_off + (size_t)desc->heads * sizeof(int32_t);
+
+    DeviceGuard guard;
+    e = guard.enter(desc->device);
+    if (e != hipSuccess) { delete p; return fail(nullptr, DIFA_ERR_HIP, hip_msg("hipSetDevice", e)); }
+    for (int s = 0; s < kSlots; ++s) {
+        Slot& sl = p->slots[s];
+        e = hipHostMalloc(&sl.h_buf, p->buf_bytes, hipHostMallocDefault);
+        if (e == hipSuccess) e = hipMalloc(&sl.d_buf, p->buf_bytes);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&sl.uploaded, hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&sl.last_use, hipEventDisableTiming);
+        if (e != hipSuccess) {
+            for (int t = 0; t <= s; ++t) free_slot(p->slots[t]);
+            delete p;
+            return fail(nullptr, e == hipErrorOutOfMemory ? DIFA_ERR_ALLOC : DIFA_ERR_HIP,
+                        hip_msg("allocating work-list buffers", e));
+        }
+    }
+    *plan_out = p;
+    return DIFA_OK;
+}
+
+extern "C" difa_status_t difa_plan_destroy(difa_plan_t* p) {
+    if (!p) return DIFA_OK;
+    DeviceGuard guard;
+    (void)guard.enter(p->desc.device);
+    (void)timing_flush(p);
+    for (Slot& s : p->slots) {
+        if (s.used && s.last_use) (void)hipEventSynchronize(s.last_use);
+        free_slot(s);
+    }
+    for (TimingPair& tp : p->pool) { (void)hipEventDestroy(tp.start); (void)hipEventDestroy(tp.stop); }
+    delete p;
+    return DIFA_OK;
+}
+
+extern "C" difa_status_t difa_plan_timing_enable(difa_plan_t* p, int32_t enable) {
+    if (!p) return DIFA_ERR_INVALID_ARG;
+    p->timing = enable != 0;
+    return DIFA_OK;
+}
+
+extern "C" difa_status_t difa_plan_timing_read(difa_plan_t* p, double* attn_ms, double* copy_ms,
+                                               int64_t* launches, int32_t reset) {
+    if (!p) return DIFA_ERR_INVALID_ARG;
+    DeviceGuard guard;
+    hipError_t e = guard.enter(p->desc.device);
+    if (e == hipSuccess) e = timing_flush(p);
+    if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("reading kernel timing events", e));
+    if (attn_ms) *attn_ms = p->attn_ms;
+    if (copy_ms) *copy_ms = p->copy_ms;
+    if (launches) *launches = p->launches;
+    if (reset) { p->attn_ms = 0; p->copy_ms = 0; p->launches = 0; }
+    return DIFA_OK;
+}
+
+extern "C" difa_status_t difa_joint_attention(difa_plan_t* p, const void* q, const void* k, const void* v,
+                                              void* out, const void* cache, const int32_t* head_plan,
+                                              int32_t n_text, int32_t n_img, const int32_t* window,
+                                              void* stream_v) {
+    if (!p) return DIFA_ERR_INVALID_ARG;
+    if (!q || !k || !v || !out || !head_plan)
+        return fail(p, DIFA_ERR_INVALID_ARG, "q, k, v, out and head_plan must not be NULL");
+    if (n_text < 0 || n_img < 0) return fail(p, DIFA_ERR_INVALID_ARG, "n_text and n_img must be >= 0");
+    const int64_t n64 = (int64_t)n_text + n_img;
+    if (n64 < 1 || n64 > p->desc.max_tokens)
+        return fail(p, DIFA_ERR_INVALID_ARG, "n_text + n_img must be in [1, max_tokens]");
+    if (out == q || out == k || out == v) return fail(p, DIFA_ERR_INVALID_ARG, "out must not alias q, k or v");
+    const int H = p->desc.heads, B = p->desc.batch, D = p->desc.head_dim, N = (int)n64;
+    bool any_cache = false;
+    for (int h = 0; h < H; ++h) {
+        const int mode = head_plan[h];
+        if (mode != DIFA_HEAD_FULL && mode != DIFA_HEAD_ARROW && mode != DIFA_HEAD_CACHE)
+            return fail(p, DIFA_ERR_INVALID_ARG, "head_plan entries must be DIFA_HEAD_FULL, _ARROW or _CACHE");
+        if (mode == DIFA_HEAD_ARROW && !window)
+            return fail(p, DIFA_ERR_INVALID_ARG, "window must not be NULL when a head is ARROW");
+        if (mode == DIFA_HEAD_ARROW && window[h] < 0)
+            return fail(p, DIFA_ERR_INVALID_ARG, "window of an ARROW head must be >= 0");
+        any_cache |= (mode == DIFA_HEAD_CACHE);
+    }
+    if (any_cache && !cache) return fail(p, DIFA_ERR_INVALID_ARG, "cache must not be NULL when a head is CACHE");
+    hipStream_t stream = (hipStream_t)stream_v;
+
+    DeviceGuard guard;
+    hipError_t e = guard.enter(p->desc.device);
+    if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("hipSetDevice", e));
+
+    // ---- memo lookup: key = effective per-head (mode, window) + token counts
+    std::vector<int32_t> key(2 * (size_t)H + 2);
+    for (int h = 0; h < H; ++h) {
+        key[2 * h] = head_plan[h];
+        key[2 * h + 1] = head_plan[h] == DIFA_HEAD_ARROW ? window[h] : 0;
+    }
+    key[2 * H] = n_text;
+    key[2 * H + 1] = n_img;
+    Slot* slot = nullptr;
+    for (Slot& s : p->slots)
+        if (s.valid && s.key == key) { slot = &s; break; }
+    if (!slot) {
+        Slot* lru = &p->slots[0];
+        for (Slot& s : p->slots) {
+            if (!s.valid) { lru = &s; break; }
+            if (s.stamp < lru->stamp) lru = &s;
+        }
+        // The buffers may still be read by launches enqueued earlier.
+        if (lru->used) {
+            e = hipEventSynchronize(lru->last_use);
+            if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("waiting for a work list in use", e));
+        }
+        lru->valid = false;
+        int32_t n_items = 0, n_copy = 0;
+        difa_status_t st = difa_worklist_build(B, H, head_plan, window, n_text, n_img, p->bm, p->bn,
+                                               (difa_work_item_t*)lru->h_buf, p->item_capacity, &n_items,
+                                               (int32_t*)((char*)lru->h_buf + p->copy_off), &n_copy);
+        if (st != DIFA_OK) return fail(p, st, "work-list compilation failed");
+        e = hipMemcpyAsync(lru->d_buf, lru->h_buf, p->buf_bytes, hipMemcpyHostToDevice, stream);
+        if (e == hipSuccess) e = hipEventRecord(lru->uploaded, stream);
+        if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("uploading the work list", e));
+        lru->key = key;
+        lru->n_items = n_items;
+        lru->n_copy = n_copy;
+        lru->upload_stream = stream;
+        lru->valid = true;
+        lru->used = true;  // the upload itself reads h_buf
+        (void)hipEventRecord(lru->last_use, stream);
+        slot = lru;
+    } else if (slot->upload_stream != stream) {
+        e = hipStreamWaitEvent(stream, slot->uploaded, 0);
+        if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("hipStreamWaitEvent", e));
+    }
+    slot->stamp = ++p->clock;
+
+    const size_t es = elem_size(p->desc.dtype);
+    int64_t sb, sh, sn;  // strides in elements
+    if (p->desc.layout == DIFA_LAYOUT_BHND) {
+        sn = D; sh = (int64_t)N * D; sb = (int64_t)H * N * D;
+    } else {
+        sh = D; sn = (int64_t)H * D; sb = (int64_t)N * H * D;
+    }
+
+    // ---- cached heads: coalesced copy (Alg. 1, O[idx] = O_cache[idx]); nothing else runs for them
+    if (slot->n_copy > 0 && cache != out) {
+        difa::CopyArgs c{};
+        c.src = cache;
+        c.dst = out;
+        c.copy_heads = (const int32_t*)((const char*)slot->d_buf + p->copy_off);
+        c.stride_b = sb * (int64_t)es; c.stride_h = sh * (int64_t)es; c.stride_n = sn * (int64_t)es;
+        c.batch = B; c.n_copy = slot->n_copy; c.n_tokens = N;
+        c.vec_per_row = (int32_t)(D * es / 16);
+        TimingPair tp{};
+        if (p->timing && (e = timing_begin(p, stream, 1, &tp)) != hipSuccess)
+            return fail(p, DIFA_ERR_HIP, hip_msg("hipEventRecord", e));
+        e = difa::launch_cache_copy(c, stream);
+        if (p->timing) { (void)hipEventRecord(tp.stop, stream); p->pending.push_back(tp); }
+        if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("cache-copy launch", e));
+    }
+
+    // ---- computed heads
+    if (slot->n_items > 0) {
+        difa::AttnArgs a{};
+        a.q = q; a.k = k; a.v = v; a.out = out;
+        a.items = (const difa_work_item_t*)slot->d_buf;
+        a.stride_b = sb; a.stride_h = sh; a.stride_n = sn;
+        a.heads = H; a.n_tokens = N; a.n_text = n_text;
+        a.scale = p->scale;
+        TimingPair tp{};
+        if (p->timing && (e = timing_begin(p, stream, 0, &tp)) != hipSuccess)
+            return fail(p, DIFA_ERR_HIP, hip_msg("hipEventRecord", e));
+        e = p->desc.dtype == DIFA_DTYPE_BF16 ? difa::launch_attn_bf16(a, D, slot->n_items, stream)
+                                             : difa::launch_attn_f32(a, D, slot->n_items, stream);
+        if (p->timing) { (void)hipEventRecord(tp.stop, stream); p->pending.push_back(tp); }
+        if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("attention launch", e));
+    }
+    e = hipEventRecord(slot->last_use, stream);
+    if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("hipEventRecord", e));
+    slot->used = true;
+    if (p->timing && p->pending.size() > 512) (void)timing_flush(p);
+    return DIFA_OK;
+}

@@ -1,0 +1,38 @@
+// Internal declarations shared by the host API and the kernel translation unit.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "difa.h"
+
+namespace difa {
+
+constexpr int kBM = 128;  // query rows per workgroup (4 wavefronts x 32 rows)
+constexpr int kBN = 64;   // keys per K/V tile
+
+// Arguments common to the attention kernels.  Strides are in elements.
+struct AttnArgs {
+    const void* q;
+    const void* k;
+    const void* v;
+    void* out;
+    const difa_work_item_t* items;  // device
+    int64_t stride_b, stride_h, stride_n;
+    int32_t heads, n_tokens, n_text;
+    float scale;  // softmax scale (natural-log domain)
+};
+
+struct CopyArgs {
+    const void* src;
+    void* dst;
+    const int32_t* copy_heads;  // device, n_copy entries
+    int64_t stride_b, stride_h, stride_n;  // in bytes
+    int32_t batch, n_copy, n_tokens, vec_per_row;  // 16-byte vectors per token row
+};
+
+// Launchers (defined in difa_kernels.hip).  All enqueue on `stream` and return the launch status.
+hipError_t launch_attn_bf16(const AttnArgs& a, int head_dim, int n_items, hipStream_t stream);
+hipError_t launch_attn_f32(const AttnArgs& a, int head_dim, int n_items, hipStream_t stream);
+hipError_t launch_cache_copy(const CopyArgs& a, hipStream_t stream);
+
+}  // namespace difa

@@ -1,0 +1,139 @@
+// Host-side compiler from a per-head plan to per-(batch, head, query tile) work records.
+//
+// Sec. 4.5 of the paper names the per-thread-block determination of the arrow pattern as
+// the overhead that shows when little work remains.  Here the pattern is resolved once per
+// distinct plan on the host, in integers: each record lists the key tiles a query tile has
+// to visit (text tiles, then the tiles its rows' bands touch) and which of them are free of
+// any masked pair, so the kernel never loads a fully masked tile and applies the element
+// mask (Sec. 3.1: text quadrants whole, image-image band |i-j| <= w) only on edge tiles.
+#include <algorithm>
+#include <vector>
+
+#include "difa.h"
+
+namespace {
+
+struct Geometry {
+    int n_text, n_tokens, bm, bn;
+};
+
+// Is there a pair (row in [i0,i1), key in [j0, j0+bn)) that must be masked out?
+// w < 0 means a full head.  Keys >= n_tokens count as masked.
+bool tile_needs_mask(const Geometry& g, int w, int i0, int i1, int j0) {
+    const int j1 = j0 + g.bn;
+    if (j1 > g.n_tokens) return true;
+    if (w < 0) return false;
+    const int qi0 = std::max(i0, g.n_text), qi1 = i1 - 1;  // image rows [qi0, qi1]
+    const int kj0 = std::max(j0, g.n_text), kj1 = j1 - 1;  // image keys [kj0, kj1]
+    if (qi0 > qi1 || kj0 > kj1) return false;
+    return (kj1 - qi0 > w) || (qi1 - kj0 > w);
+}
+
+// Mask-free tiles of a range [begin, end): for the first range the mask-free prefix, for the
+// second the longest run of consecutive mask-free tiles.  Treating a mask-free tile as masked
+// is always safe, so any sub-run is a valid answer.
+void mask_free_run(const Geometry& g, int w, int i0, int i1, int begin, int end, bool prefix_only,
+                   int* run_begin, int* run_end) {
+    int best_b = begin, best_e = begin;
+    int t = begin;
+    while (t < end) {
+        if (tile_needs_mask(g, w, i0, i1, t * g.bn)) {
+            if (prefix_only) break;
+            ++t;
+            continue;
+        }
+        int e = t;
+        while (e < end && !tile_needs_mask(g, w, i0, i1, e * g.bn)) ++e;
+        if (e - t > best_e - best_b) { best_b = t; best_e = e; }
+        if (prefix_only) break;
+        t = e;
+    }
+    *run_begin = best_b;
+    *run_end = best_e;
+}
+
+}  // namespace
+
+extern "C" int32_t difa_tile_shape(int32_t head_dim, int32_t dtype, int32_t* bm, int32_t* bn) {
+    if ((head_dim != 64 && head_dim != 128) || (dtype != DIFA_DTYPE_BF16 && dtype != DIFA_DTYPE_F32))
+        return 1;
+    if (bm) *bm = 128;
+    if (bn) *bn = 64;
+    return 0;
+}
+
+extern "C" difa_status_t difa_worklist_build(int32_t batch, int32_t heads, const int32_t* head_plan,
+                                             const int32_t* window, int32_t n_text, int32_t n_img,
+                                             int32_t bm, int32_t bn, difa_work_item_t* items,
+                                             int32_t capacity, int32_t* n_items_out,
+                                             int32_t* copy_heads, int32_t* n_copy_out) {
+    if (!head_plan || !n_items_out || batch < 1 || heads < 1 || n_text < 0 || n_img < 0 ||
+        bm < 1 || bn < 1 || capacity < 0 || (capacity > 0 && !items))
+        return DIFA_ERR_INVALID_ARG;
+    const int64_t n64 = (int64_t)n_text + (int64_t)n_img;
+    if (n64 < 1 || n64 > (int64_t)1 << 30) return DIFA_ERR_INVALID_ARG;
+    for (int h = 0; h < heads; ++h) {
+        const int mode = head_plan[h];
+        if (mode != DIFA_HEAD_FULL && mode != DIFA_HEAD_ARROW && mode != DIFA_HEAD_CACHE)
+            return DIFA_ERR_INVALID_ARG;
+        if (mode == DIFA_HEAD_ARROW && (!window || window[h] < 0)) return DIFA_ERR_INVALID_ARG;
+    }
+    const Geometry g{n_text, (int)n64, bm, bn};
+    const int n_q_tiles = (g.n_tokens + bm - 1) / bm;
+    const int n_kv_tiles = (g.n_tokens + bn - 1) / bn;
+    const int text_tiles = (n_text + bn - 1) / bn;  // tiles that hold at least one text key
+
+    std::vector<difa_work_item_t> recs;
+    int n_copy = 0;
+    for (int h = 0; h < heads; ++h) {
+        const int mode = head_plan[h];
+        if (mode == DIFA_HEAD_CACHE) {
+            if (copy_heads) copy_heads[n_copy] = h;
+            ++n_copy;
+            continue;
+        }
+        // A band that covers the whole image is full attention.
+        const bool full = (mode == DIFA_HEAD_FULL) || (window[h] >= n_img - 1);
+        const int w = full ? -1 : window[h];
+        for (int qt = 0; qt < n_q_tiles; ++qt) {
+            const int i0 = qt * bm, i1 = std::min(i0 + bm, g.n_tokens);
+            difa_work_item_t r{};
+            r.q_tile = qt;
+            r.window = w;
+            if (full) {
+                r.kv0_end = n_kv_tiles;
+                r.kv1_begin = r.kv1_end = n_kv_tiles;
+            } else {
+                r.kv0_end = text_tiles;
+                if (i0 < n_text) {  // the tile holds text queries: they see every key
+                    r.kv1_begin = text_tiles;
+                    r.kv1_end = n_kv_tiles;
+                } else {
+                    const int lo = std::max(n_text, i0 - w);
+                    const int hi = std::min(g.n_tokens - 1, (i1 - 1) + w);
+                    r.kv1_begin = std::max(text_tiles, lo / bn);
+                    r.kv1_end = std::max(r.kv1_begin, hi / bn + 1);
+                }
+            }
+            int b0, e0;
+            mask_free_run(g, w, i0, i1, 0, r.kv0_end, true, &b0, &e0);
+            r.nm0_end = e0;
+            mask_free_run(g, w, i0, i1, r.kv1_begin, r.kv1_end, false, &r.nm1_begin, &r.nm1_end);
+            r.n_tiles = r.kv0_end + (r.kv1_end - r.kv1_begin);
+            for (int b = 0; b < batch; ++b) {
+                r.bh = b * heads + h;
+                recs.push_back(r);
+            }
+        }
+    }
+    // Heaviest records first: the hardware hands workgroups out in index order, so the long
+    // full-attention tiles start early and the short band tiles fill the tail.
+    std::stable_sort(recs.begin(), recs.end(), [](const difa_work_item_t& a, const difa_work_item_t& b) {
+        return a.n_tiles > b.n_tiles;
+    });
+    *n_items_out = (int32_t)recs.size();
+    if (n_copy_out) *n_copy_out = n_copy;
+    if ((int64_t)recs.size() > capacity) return capacity == 0 && !items ? DIFA_OK : DIFA_ERR_ALLOC;
+    std::copy(recs.begin(), recs.end(), items);
+    return DIFA_OK;
+}

@@ -1,0 +1,247 @@
+"""Parity of the HIP library (through the C ABI) against the CPU oracle, element by element.
+
+Bars: max-abs 2e-2 for bf16 inputs (fp32 accumulation), 1e-5 for the fp32 debug path, cached
+heads bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2503_22796_amd import workloads as W
+from util import (ARROW, CACHE, FULL, TOL_BF16, TOL_F32, boundary_rows, check_against_oracle,
+                  gpu_joint_attention)
+
+pytestmark = pytest.mark.gpu
+
+
+def small_workload(B, H, D, n_text, n_img, modes, wins, seed, positional=False):
+    return W.Workload("case", B, H, D, n_text, n_img, np.asarray(modes, np.int32), np.asarray(wins, np.int32),
+                      seed=seed, positional=positional)
+
+
+def run_case(wl, dtype=torch.bfloat16, layout="bhnd", rows=None, scale=0.0, tol=None):
+    q, k, v = W.make_qkv(wl, dtype=dtype)
+    cache = W.make_cache(wl, dtype=dtype) if (wl.head_plan == CACHE).any() else None
+    out = gpu_joint_attention(q, k, v, cache, wl.head_plan, wl.window, wl.n_text, wl.n_img, scale=scale,
+                              layout=layout)
+    tol = tol if tol is not None else (TOL_BF16 if dtype == torch.bfloat16 else TOL_F32)
+    err = check_against_oracle(out, q, k, v, cache, wl.head_plan, wl.window, wl.n_text, wl.n_img,
+                               scale=(scale if scale > 0 else None), rows=rows, tol=tol)
+    print(f"{wl.name}: dtype={dtype} layout={layout} max_abs_err={err:.3e} max|out|={float(out.float().abs().max()):.2f}",
+          flush=True)
+    return out
+
+
+# ----------------------------------------------------------------------------- the named configs
+def test_tiny_bf16():
+    run_case(W.tiny())
+
+
+def test_tiny_fp32_debug_path():
+    run_case(W.tiny(), dtype=torch.float32)
+
+
+def test_sd3_1k_all_rows():
+    run_case(W.sd3_1k())
+
+
+def test_flux_1k_all_rows():
+    run_case(W.flux_1k())
+
+
+def test_flux_2k_mixed_sampled_rows():
+    wl = W.flux_2k_mixed()
+    rows = boundary_rows(wl.n_text, wl.n_img, wl.window[wl.head_plan == ARROW], extra=96, seed=4)
+    run_case(wl, rows=rows)
+
+
+def test_flux_2k_full_sampled_rows():
+    wl = W.flux_2k_full()
+    rows = boundary_rows(wl.n_text, wl.n_img, [], extra=48, seed=5)
+    run_case(wl, rows=rows)
+
+
+# ----------------------------------------------------------------------------- shapes and edges
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("n_text,n_img,wins", [
+    (0, 300, [0, 1, 70]),          # no text: pure band, first band tile has fully masked rows
+    (77, 0, [0, 5, 9]),            # no image tokens: every head is full attention
+    (1, 1, [0, 0, 0]),             # two tokens
+    (64, 256, [63, 64, 65]),       # band edges on tile edges
+    (333, 1000, [7, 130, 998]),    # text edge mid-tile, ragged tail, window ~ n_img
+    (130, 515, [200, 514, 9999]),  # w >= n_img - 1 is full attention
+])
+def test_edge_shapes_bf16(D, n_text, n_img, wins):
+    wl = small_workload(2, 4, D, n_text, n_img, [FULL, ARROW, ARROW, ARROW], [0] + wins, seed=100 + n_img)
+    run_case(wl)
+
+
+def test_single_token():
+    wl = small_workload(1, 2, 64, 1, 0, [FULL, ARROW], [0, 3], seed=7)
+    run_case(wl)
+    wl = small_workload(1, 2, 64, 0, 1, [FULL, ARROW], [0, 0], seed=8)
+    run_case(wl)
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_fp32_debug_path_mid_size(D):
+    wl = small_workload(2, 5, D, 45, 400, [FULL, ARROW, ARROW, CACHE, ARROW], [0, 0, 33, 0, 399], seed=21,
+                        positional=True)
+    run_case(wl, dtype=torch.float32)
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_bnhd_layout(dtype):
+    wl = small_workload(2, 6, 64, 50, 256, [FULL, ARROW, CACHE, ARROW, CACHE, FULL], [0, 17, 0, 100, 0, 0],
+                        seed=31, positional=True)
+    run_case(wl, dtype=dtype, layout="bnhd")
+
+
+def test_softmax_scale_override():
+    wl = small_workload(1, 2, 64, 20, 144, [FULL, ARROW], [0, 12], seed=41)
+    run_case(wl, scale=0.05)
+
+
+def test_peaked_rows_with_large_values():
+    # positional term makes rows sharply peaked; large values stress the P rounding and rescale
+    wl = small_workload(1, 3, 128, 64, 1024, [FULL, ARROW, ARROW], [0, 64, 300], seed=51, positional=True)
+    run_case(wl)
+
+
+# ----------------------------------------------------------------------------- invariants on the GPU
+def test_arrow_covering_window_equals_full_on_gpu():
+    wl = small_workload(1, 3, 128, 70, 400, [FULL, ARROW, ARROW], [0, 399, 5000], seed=61)
+    q, k, v = W.make_qkv(wl)
+    q[:, 1:] = q[:, :1]; k[:, 1:] = k[:, :1]; v[:, 1:] = v[:, :1]
+    out = gpu_joint_attention(q, k, v, None, wl.head_plan, wl.window, wl.n_text, wl.n_img)
+    assert torch.equal(out[:, 0], out[:, 1]) and torch.equal(out[:, 0], out[:, 2])
+
+
+def test_keys_outside_band_do_not_matter_on_gpu():
+    n_text, n_img, w = 100, 900, 150
+    wl = small_workload(1, 1, 128, n_text, n_img, [ARROW], [w], seed=71)
+    q, k, v = W.make_qkv(wl)
+    base = gpu_joint_attention(q, k, v, None, wl.head_plan, wl.window, n_text, n_img)
+    i = n_text + 500
+    k2, v2 = k.clone(), v.clone()
+    for j in (i + w + 1, i - w - 1):
+        k2[0, 0, j] = 40.0
+        v2[0, 0, j] = -30.0
+    got = gpu_joint_attention(q, k2, v2, None, wl.head_plan, wl.window, n_text, n_img)
+    assert torch.equal(got[0, 0, i], base[0, 0, i])
+    k3 = k.clone()
+    k3[0, 0, i + w] = 40.0
+    got3 = gpu_joint_attention(q, k3, v, None, wl.head_plan, wl.window, n_text, n_img)
+    assert not torch.equal(got3[0, 0, i], base[0, 0, i])
+
+
+def test_cache_heads_bit_exact_and_cache_contents_never_leak():
+    wl = small_workload(2, 4, 64, 33, 300, [CACHE, FULL, CACHE, ARROW], [0, 0, 0, 40], seed=81)
+    q, k, v = W.make_qkv(wl)
+    cache = W.make_cache(wl)
+    cache[:, 1] = float("nan")
+    cache[:, 3] = float("inf")
+    cache.view(torch.int16)[0, 0, 0, 0] = 0x7FC1     # NaN payload must survive
+    out = gpu_joint_attention(q, k, v, cache, wl.head_plan, wl.window, wl.n_text, wl.n_img)
+    for h in (0, 2):
+        assert torch.equal(out[:, h].view(torch.int16), cache[:, h].view(torch.int16))
+    check_against_oracle(out, q, k, v, cache, wl.head_plan, wl.window, wl.n_text, wl.n_img)
+
+
+def test_all_heads_cached_launches_only_the_copy():
+    wl = small_workload(1, 3, 128, 10, 200, [CACHE, CACHE, CACHE], [0, 0, 0], seed=91)
+    q, k, v = W.make_qkv(wl)
+    cache = W.make_cache(wl)
+    out = gpu_joint_attention(q, k, v, cache, wl.head_plan, wl.window, wl.n_text, wl.n_img)
+    assert torch.equal(out.view(torch.int16), cache.view(torch.int16))
+
+
+def test_out_may_alias_cache():
+    wl = small_workload(1, 3, 64, 20, 300, [CACHE, ARROW, FULL], [0, 25, 0], seed=101)
+    q, k, v = W.make_qkv(wl)
+    cache = W.make_cache(wl)
+    out = gpu_joint_attention(q, k, v, cache, wl.head_plan, wl.window, wl.n_text, wl.n_img,
+                              alias_out_to_cache=True)
+    check_against_oracle(out, q, k, v, cache, wl.head_plan, wl.window, wl.n_text, wl.n_img)
+
+
+# ----------------------------------------------------------------------------- the plan object
+def test_plan_reuse_many_plans_and_a_side_stream():
+    from paper_2503_22796_amd import binding as B
+    n_text, n_img, H, D = 40, 529, 4, 128
+    N = n_text + n_img
+    base = small_workload(1, H, D, n_text, n_img, [FULL] * H, [0] * H, seed=111, positional=True)
+    q, k, v = W.make_qkv(base)
+    cache = W.make_cache(base)
+    plan = B.difa_plan_create(1, H, D, max_tokens=N)
+    side = torch.cuda.Stream()
+    try:
+        rng = np.random.Generator(np.random.PCG64(5))
+        cases = []
+        for it in range(12):                      # more distinct plans than the memo keeps
+            hp = rng.integers(0, 3, size=H).astype(np.int32)
+            win = rng.integers(0, 300, size=H).astype(np.int32)
+            cases.append((hp, win))
+        for rep in range(2):                      # second pass: evicted plans are rebuilt
+            for n, (hp, win) in enumerate(cases):
+                stream = side if n % 2 else None
+                out = gpu_joint_attention(q, k, v, cache, hp, win, n_text, n_img, plan=plan, stream=stream)
+                check_against_oracle(out, q, k, v, cache, hp, win, n_text, n_img)
+        # a shorter sequence on the same plan object
+        wl2 = small_workload(1, H, D, 8, 100, [ARROW, FULL, CACHE, ARROW], [3, 0, 0, 50], seed=112)
+        q2, k2, v2 = W.make_qkv(wl2)
+        c2 = W.make_cache(wl2)
+        out = gpu_joint_attention(q2, k2, v2, c2, wl2.head_plan, wl2.window, 8, 100, plan=plan)
+        check_against_oracle(out, q2, k2, v2, c2, wl2.head_plan, wl2.window, 8, 100)
+    finally:
+        B.difa_plan_destroy(plan)
+
+
+def test_argument_errors_launch_nothing():
+    from paper_2503_22796_amd import binding as B
+    H, D, N = 2, 64, 32
+    plan = B.difa_plan_create(1, H, D, max_tokens=N)
+    dev = torch.device("cuda:0")
+    q = torch.zeros(1, H, N, D, dtype=torch.bfloat16, device=dev)
+    out = torch.full_like(q, 7.0)
+    try:
+        bad = [
+            dict(head_plan=[0, 3], window=[0, 0]),                 # unknown mode
+            dict(head_plan=[1, 0], window=[-2, 0]),                # negative window
+            dict(head_plan=[1, 0], window=None),                   # arrow without windows
+            dict(head_plan=[2, 0], window=[0, 0]),                 # cache head, no cache tensor
+            dict(head_plan=[0, 0], window=[0, 0], n_text=30, n_img=30),   # beyond max_tokens
+            dict(head_plan=[0, 0], window=[0, 0], n_text=0, n_img=0),
+            dict(head_plan=[0, 0], window=[0, 0], n_text=-1, n_img=5),
+        ]
+        for kw in bad:
+            args = dict(n_text=16, n_img=16)
+            args.update(kw)
+            with pytest.raises(B.DifaError) as ei:
+                B.difa_joint_attention(plan, q, q, q, out, None, args["head_plan"], args["n_text"],
+                                       args["n_img"], args["window"])
+            assert ei.value.status == B.DIFA_ERR_INVALID_ARG
+            assert B.difa_last_error(plan) != ""
+        with pytest.raises(B.DifaError):
+            B.difa_joint_attention(plan, q, q, q, q, None, [0, 0], 16, 16, [0, 0])   # out aliases q
+        torch.cuda.synchronize()
+        assert bool((out == 7.0).all())
+    finally:
+        B.difa_plan_destroy(plan)
+
+
+def test_kernel_timing_hook():
+    from paper_2503_22796_amd import binding as B
+    wl = small_workload(1, 4, 128, 64, 1024, [FULL, ARROW, CACHE, FULL], [0, 100, 0, 0], seed=121)
+    q, k, v = (t.cuda() for t in W.make_qkv(wl))
+    cache = W.make_cache(wl).cuda()
+    out = torch.empty_like(q)
+    plan = B.difa_plan_create(1, 4, 128, max_tokens=wl.N)
+    try:
+        B.difa_plan_timing_enable(plan, True)
+        for _ in range(3):
+            B.difa_joint_attention(plan, q, k, v, out, cache, wl.head_plan, wl.n_text, wl.n_img, wl.window)
+        attn_ms, copy_ms, launches = B.difa_plan_timing_read(plan)
+        assert launches == 3 and attn_ms > 0 and copy_ms > 0
+        assert B.difa_plan_timing_read(plan)[2] == 0
+    finally:
+        B.difa_plan_destroy(plan)

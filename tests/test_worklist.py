@@ -1,0 +1,110 @@
+"""Host work-list compiler against a brute-force enumeration of allowed pairs per tile."""
+import itertools
+
+import numpy as np
+import pytest
+
+from paper_2503_22796_amd import binding as B
+
+FULL, ARROW, CACHE = 0, 1, 2
+
+
+def allowed(mode, w, n_text, i, j):
+    if mode == FULL:
+        return True
+    return i < n_text or j < n_text or abs(i - j) <= w
+
+
+def brute_tiles(mode, w, n_text, N, i0, i1, bn):
+    """(tiles with at least one allowed pair, tiles with every pair allowed and no key >= N)."""
+    some, every = set(), set()
+    for t in range((N + bn - 1) // bn):
+        js = range(t * bn, (t + 1) * bn)
+        flags = [(j < N) and allowed(mode, w, n_text, i, j) for i in range(i0, i1) for j in js]
+        if any(flags):
+            some.add(t)
+        if all(flags):
+            every.add(t)
+    return some, every
+
+
+CASES = [
+    # n_text, n_img, bm, bn, [(mode, w)...]
+    (5, 40, 8, 4, [(FULL, 0), (ARROW, 0), (ARROW, 3), (ARROW, 9), (CACHE, 0), (ARROW, 39), (ARROW, 100)]),
+    (0, 33, 8, 4, [(ARROW, 0), (ARROW, 5), (FULL, 0)]),
+    (16, 64, 16, 8, [(FULL, 0), (ARROW, 8), (ARROW, 16), (CACHE, 0)]),
+    (7, 0, 8, 4, [(ARROW, 2), (FULL, 0)]),
+    (3, 1, 8, 4, [(ARROW, 0)]),
+    (12, 50, 8, 8, [(ARROW, 1), (ARROW, 7), (ARROW, 8), (ARROW, 20)]),
+    (9, 31, 4, 8, [(ARROW, 2), (ARROW, 11)]),
+]
+
+
+@pytest.mark.parametrize("n_text,n_img,bm,bn,heads", CASES)
+@pytest.mark.parametrize("batch", [1, 2])
+def test_records_match_brute_force(n_text, n_img, bm, bn, heads, batch):
+    N = n_text + n_img
+    hp = [m for m, _ in heads]
+    win = [w for _, w in heads]
+    H = len(heads)
+    st, items, copy_heads = B.difa_worklist_build(batch, H, hp, win, n_text, n_img, bm, bn)
+    assert st == B.DIFA_OK
+    assert list(copy_heads) == [h for h in range(H) if hp[h] == CACHE]
+    n_q = (N + bm - 1) // bm
+    computed = [h for h in range(H) if hp[h] != CACHE]
+    assert len(items) == batch * len(computed) * n_q
+    seen = set()
+    tiles = [int(x) for x in items["n_tiles"]]
+    assert tiles == sorted(tiles, reverse=True), "records must be ordered heaviest first"
+    for r in items:
+        b, h = divmod(int(r["bh"]), H)
+        assert 0 <= b < batch and h in computed
+        key = (b, h, int(r["q_tile"]))
+        assert key not in seen
+        seen.add(key)
+        i0, i1 = int(r["q_tile"]) * bm, min(N, (int(r["q_tile"]) + 1) * bm)
+        mode, w = hp[h], win[h]
+        some, every = brute_tiles(mode, w, n_text, N, i0, i1, bn)
+        assert r["kv1_begin"] >= r["kv0_end"]
+        visited = set(range(0, r["kv0_end"])) | set(range(r["kv1_begin"], r["kv1_end"]))
+        assert visited == some, "visited tiles must be exactly the tiles that hold an allowed pair"
+        assert r["n_tiles"] == len(visited)
+        mask_free = set(range(0, min(r["nm0_end"], r["kv0_end"]))) | \
+            set(range(max(r["nm1_begin"], r["kv1_begin"]), min(r["nm1_end"], r["kv1_end"])))
+        assert mask_free <= every, "a tile flagged mask-free holds a masked pair"
+        assert mask_free == (every & visited), "every mask-free tile should be recognised as such"
+        if mode == ARROW and w < n_img - 1:
+            assert r["window"] == w
+        else:
+            assert r["window"] == -1
+    assert len(seen) == len(items)
+
+
+def test_flux_2k_shape_tile_counts():
+    # image-only query tile of an arrow head visits 8 text tiles + the band tiles
+    bm, bn = B.difa_tile_shape(128)
+    st, items, _ = B.difa_worklist_build(1, 2, [ARROW, FULL], [512, 0], 512, 16384, bm, bn)
+    assert st == B.DIFA_OK
+    N = 16896
+    assert len(items) == 2 * ((N + bm - 1) // bm)
+    full = items[items["window"] == -1]
+    assert (full["n_tiles"] == N // bn).all() and (full["nm0_end"] == N // bn).all()
+    arrow = items[items["window"] == 512]
+    mid = arrow[arrow["q_tile"] == 60][0]
+    i0 = 60 * bm
+    lo, hi = i0 - 512, i0 + bm - 1 + 512
+    assert mid["kv0_end"] == 8 and mid["nm0_end"] == 8
+    assert mid["kv1_begin"] == lo // bn and mid["kv1_end"] == hi // bn + 1
+    # the paper's "single masking operation": only the tiles the two band edges cross are masked
+    masked = mid["n_tiles"] - 8 - (mid["nm1_end"] - mid["nm1_begin"])
+    assert 0 < masked <= 2 * (bm // bn + 1)
+
+
+def test_invalid_plans_are_rejected():
+    for hp, win in (([3], [0]), ([ARROW], [-1]), ([-1], [0])):
+        st, _, _ = B.difa_worklist_build(1, 1, hp, win, 4, 4, 8, 4)
+        assert st == B.DIFA_ERR_INVALID_ARG
+    st, _, _ = B.difa_worklist_build(1, 1, [ARROW], None, 4, 4, 8, 4)
+    assert st == B.DIFA_ERR_INVALID_ARG
+    st, _, _ = B.difa_worklist_build(1, 1, [FULL], [0], 0, 0, 8, 4)
+    assert st == B.DIFA_ERR_INVALID_ARG
