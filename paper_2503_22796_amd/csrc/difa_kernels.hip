@@ -2,6 +2,8 @@
 //   attn_bf16_kernel  -- full / arrow heads, bf16 MFMA with fp32 accumulation
 //   attn_f32_kernel   -- the same result in plain fp32 arithmetic (slow debug path)
 //   cache_copy_kernel -- cached heads: out[b,h] = cache[b,h] (Alg. 1, last statement)
+#include <type_traits>
+
 #include "difa_internal.h"
 
 namespace difa {
@@ -19,32 +21,60 @@ __device__ __forceinline__ float xchg32(float x) {
 // ------------------------------------------------------------------------------------------
 // bf16 MFMA attention.
 //
-// One workgroup = 4 wavefronts = one 128-row query tile of one (batch, head); wavefront w owns
-// rows 32w..32w+31.  Key/value tiles of 64 keys are staged through LDS and visited in the order
-// the host-compiled work record lists them (text tiles, then the band tiles), so a tile with no
-// allowed pair is never loaded (Sec. 3.1 / 3.3: block-sparse band).
+// One workgroup = 4 wavefronts (one per SIMD) = one 256-row query tile of one (batch, head);
+// wavefront w owns rows 64w..64w+63 as two 32-row blocks.  Key/value tiles of 64 keys go through
+// a 3-stage LDS ring and are visited in the order the host-compiled work record lists them
+// (text tiles, then the band tiles), so a tile with no allowed pair is never loaded
+// (Sec. 3.1 / 3.3: block-sparse band).
+//
+// Why 64 rows per wavefront: LDS delivers 128 B/clk/CU, i.e. one 16-byte-per-lane operand read
+// per MFMA issue slot of the CU.  With 32 rows per wavefront every MFMA needs a fresh K or V
+// operand from LDS and the LDS port, not the matrix core, sets the pace; with 64 rows each
+// operand read feeds two MFMAs.
 //
 // Scores are produced transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: a lane then holds
 // 16 keys of ONE query (column = lane % 32), so the softmax row statistics are per-lane scalars
 // and need one exchange between the wavefront halves.  The same register layout is exactly the
-// B operand of O^T = V^T P^T, so P never goes through LDS.
+// B operand of O^T = V^T P^T, so P never goes through LDS.  V stays row-major [key][feature] in
+// LDS and its transposed operand comes from ds_read_b64_tr_b16.
+//
+// Software pipeline inside a wavefront: S^T of tile t+1 (MFMA) is issued in the same basic block
+// as the softmax of tile t (VALU), so the two pipes overlap without a second wavefront.
 // ------------------------------------------------------------------------------------------
-template <int D>
-struct TileCfg {
-    static constexpr int KSTR = D + 8;      // bf16 per K row in LDS (+16 B: conflict-free 16 B reads)
-    static constexpr int VSTR = kBN + 4;    // bf16 per V^T row in LDS (+8 B: conflict-free 8 B reads)
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+
+// LDS transpose read: within each group of 16 lanes, lane i receives element (i % 4) of the four
+// 8-byte rows that lanes (i/4), 4+(i/4), 8+(i/4), 12+(i/4) of the group point at.
+__device__ __forceinline__ bf16x4 lds_read_tr16(const __bf16* p) {
+    const shortx4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (shortx4 __attribute__((address_space(3)))*)(p));
+    return __builtin_bit_cast(bf16x4, r);
+}
+
+struct RowState {
+    float m;       // reference maximum (log2 domain) the weights are expressed against
+    float l;       // running sum of this lane's half of the keys
+    int lo;        // band of allowed image keys is [lo, lo + span]; text keys [0, n_text) always allowed
+    unsigned span;
 };
 
 template <int D>
-__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
-    constexpr int KS = D / 16;        // MFMA k-steps of S^T = K Q^T
-    constexpr int DB = D / 32;        // 32-row blocks of O^T
-    constexpr int KSTR = TileCfg<D>::KSTR, VSTR = TileCfg<D>::VSTR;
-    constexpr int CPR = D / 8;        // 16-byte chunks per K/V row
+__global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
+    constexpr int KS = D / 16;              // MFMA k-steps of S^T = K Q^T
+    constexpr int DB = D / 32;              // 32-row blocks of O^T
+    constexpr int CPR = D / 8;              // 16-byte chunks per K/V row
     constexpr int LOADS = kBN * CPR / 256;  // 16-byte loads per thread per tensor per tile
+    constexpr int TILE = kBN * D;           // elements of one K or V tile
+    constexpr int NST = 3;                  // LDS ring depth
+    constexpr float kBump = 8.0f;           // the reference maximum moves only when exceeded by 2^8
 
-    __shared__ __attribute__((aligned(16))) __bf16 Ks[kBN * KSTR];
-    __shared__ __attribute__((aligned(16))) __bf16 Vt[D * VSTR];
+    // K rows: 16-byte chunk c of row r is stored at chunk c ^ (r % CPR)       (conflict-free b128 reads)
+    // V rows: chunk c of row r is stored at chunk c ^ (2 * (r % 4))          (conflict-free transpose reads)
+    __shared__ __attribute__((aligned(16))) __bf16 Ksm[NST * TILE];
+    __shared__ __attribute__((aligned(16))) __bf16 Vsm[NST * TILE];
 
     const difa_work_item_t it = a.items[blockIdx.x];
     if (it.q_tile < 0) return;
@@ -58,170 +88,244 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     const __bf16* __restrict__ vg = (const __bf16*)a.v + base;
     __bf16* __restrict__ og = (__bf16*)a.out + base;
 
-    const int row0 = it.q_tile * kBM + wave * 32;           // first query row of this wavefront
-    const int i_raw = row0 + l32;
-    const int i = i_raw < N ? i_raw : N - 1;                // rows past the end recompute row N-1
+    const int row0 = it.q_tile * kBM + wave * 64;           // first query row of this wavefront
     const float c = a.scale * 1.44269504088896340736f;      // scores are kept in the log2 domain
 
-    // allowed keys of this lane's query: [0, n_text) and [lo, hi]
-    int lo, hi;
-    if (it.window < 0 || i < n_text) { lo = 0; hi = N - 1; }
-    else { lo = i - it.window; hi = i + it.window < N - 1 ? i + it.window : N - 1; }
-    const unsigned span = (unsigned)(hi - lo);              // key j is in the band iff (unsigned)(j - lo) <= span
-
-    // Q operand (B of S^T = K Q^T): column = query l32, k-slots 8*half..8*half+7 of each 16-wide step
-    bf16x8 qf[KS];
-    {
+    // ---- per-lane query rows (two: one per 32-row block), their allowed key ranges, Q operands
+    RowState rs[2];
+    bf16x8 qf[2][KS];
+    int i_raw[2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        i_raw[qb] = row0 + 32 * qb + l32;
+        const int i = i_raw[qb] < N ? i_raw[qb] : N - 1;    // rows past the end recompute row N-1
+        int lo, hi;
+        if (it.window < 0 || i < n_text) { lo = 0; hi = N - 1; }
+        else { lo = i - it.window; hi = i + it.window < N - 1 ? i + it.window : N - 1; }
+        rs[qb].lo = lo;
+        rs[qb].span = (unsigned)(hi - lo);                  // key j is in the band iff (unsigned)(j-lo) <= span
+        rs[qb].m = -1.0e30f;                                // finite: exp2(-inf - m) must be 0, not NaN
+        rs[qb].l = 0.f;
+        // B operand of S^T = K Q^T: column = query l32, k-slots 8*half..8*half+7 of each 16-wide step
         const __bf16* qrow = qg + (int64_t)i * a.stride_n + 8 * half;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8*)(qrow + 16 * ks);
+        for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = *(const bf16x8*)(qrow + 16 * ks);
     }
 
-    floatx16 o[DB];
+    // ---- per-lane LDS offsets (elements, within one stage)
+    int koff[KS];                                           // A operand of S^T: row l32, chunk 2*ks+half
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) koff[ks] = l32 * D + 8 * ((2 * ks + half) ^ (l32 & (CPR - 1)));
+    int voff[DB];                                           // transpose read: row 4*half + s/4, 4 features
+    {
+        const int blk = lane >> 4, s16 = lane & 15;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            const int chunk = 4 * db + 2 * (blk & 1) + ((s16 & 3) >> 1);
+            voff[db] = (4 * half + (s16 >> 2)) * D + 8 * (chunk ^ (2 * (s16 >> 2))) + 4 * (s16 & 1);
+        }
+    }
+
+    floatx16 o[DB][2];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
-    float m = -1.0e30f;   // running maximum (log2 domain); finite so that exp2(-inf - m) is 0, not NaN
-    float l = 0.f;        // running sum of this lane's half of the keys
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[db][qb][r] = 0.f;
 
     const int n_iter = it.kv0_end + (it.kv1_end - it.kv1_begin);
-    bf16x8 kreg[LOADS], vreg[LOADS];
-
-    auto tile_of = [&](int idx) { return idx < it.kv0_end ? idx : it.kv1_begin + (idx - it.kv0_end); };
-    auto load_tile = [&](int t) {
-#pragma unroll
-        for (int u = 0; u < LOADS; ++u) {
-            const int ch = tid + 256 * u;
-            const int r = ch / CPR, cc = ch - r * CPR;
-            int j = t * kBN + r;
-            j = j < N ? j : N - 1;                          // tail keys are masked later
-            const int64_t off = (int64_t)j * a.stride_n + 8 * cc;
-            kreg[u] = *(const bf16x8*)(kg + off);
-            vreg[u] = *(const bf16x8*)(vg + off);
-        }
+    auto tile_of = [&](int idx) {
+        idx = idx < n_iter ? idx : n_iter - 1;              // past the end: reload the last tile (unused)
+        return idx < it.kv0_end ? idx : it.kv1_begin + (idx - it.kv0_end);
     };
-    auto store_tile = [&]() {
-#pragma unroll
-        for (int u = 0; u < LOADS; ++u) {
-            const int ch = tid + 256 * u;
-            const int r = ch / CPR, cc = ch - r * CPR;
-            *(bf16x8*)&Ks[r * KSTR + 8 * cc] = kreg[u];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) Vt[(8 * cc + e) * VSTR + r] = vreg[u][e];   // transpose
-        }
-    };
-
-    if (n_iter > 0) {
-        load_tile(tile_of(0));
-        store_tile();
-    }
-    __syncthreads();
-
-    for (int idx = 0; idx < n_iter; ++idx) {
+    auto tile_masked = [&](int idx) {
         const int t = tile_of(idx);
-        const bool more = idx + 1 < n_iter;
-        if (more) load_tile(tile_of(idx + 1));              // global loads overlap the math below
-
-        const bool masked = idx < it.kv0_end ? (t >= it.nm0_end) : (t < it.nm1_begin || t >= it.nm1_end);
-        const int j0 = t * kBN;
-        // A masked tile may hold no allowed pair for this wavefront's 32 rows: skip its math.
-        bool active = true;
-        if (masked && it.window >= 0) {
-            const int r_first = row0 < N ? row0 : N - 1;
-            const int r_last = row0 + 31 < N ? row0 + 31 : N - 1;
-            const int j_last = (j0 + kBN < N ? j0 + kBN : N) - 1;
-            active = (r_first < n_text) || (j0 < n_text) ||
-                     (j0 <= r_last + it.window && j_last >= r_first - it.window);
+        return idx < it.kv0_end ? (t >= it.nm0_end) : (t < it.nm1_begin || t >= it.nm1_end);
+    };
+    // ---- global -> registers -> LDS staging of one K/V tile.  Buffer loads: one descriptor per
+    // tensor for this (batch, head), a per-thread byte offset that is constant over the loop plus the
+    // tile's byte offset; rows past the last token read as zero (they are masked later).
+    const unsigned head_bytes = (unsigned)(((int64_t)(N - 1) * a.stride_n + D) * 2);
+    const __amdgpu_buffer_rsrc_t krsrc = __builtin_amdgcn_make_buffer_rsrc((void*)kg, 0, head_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t vrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)vg, 0, head_bytes, 0x00020000);
+    unsigned goff[LOADS];
+#pragma unroll
+    for (int u = 0; u < LOADS; ++u) {
+        const int ch = tid + 256 * u;
+        const int r = ch / CPR, cc = ch - r * CPR;
+        goff[u] = (unsigned)(r * (int)a.stride_n + 8 * cc) * 2u;
+    }
+    const unsigned tile_bytes = (unsigned)(kBN * (int)a.stride_n) * 2u;
+    uintx4 kreg[LOADS], vreg[LOADS];
+    auto load_tile = [&](int t) {
+        const unsigned tb = (unsigned)t * tile_bytes;
+#pragma unroll
+        for (int u = 0; u < LOADS; ++u) {
+            kreg[u] = __builtin_amdgcn_raw_buffer_load_b128(krsrc, goff[u] + tb, 0, 0);
+            vreg[u] = __builtin_amdgcn_raw_buffer_load_b128(vrsrc, goff[u] + tb, 0, 0);
         }
+    };
+    auto store_tile = [&](int stage) {
+#pragma unroll
+        for (int u = 0; u < LOADS; ++u) {
+            const int ch = tid + 256 * u;
+            const int r = ch / CPR, cc = ch - r * CPR;
+            *(uintx4*)&Ksm[stage * TILE + r * D + 8 * (cc ^ (r & (CPR - 1)))] = kreg[u];
+            *(uintx4*)&Vsm[stage * TILE + r * D + 8 * (cc ^ (2 * (r & 3)))] = vreg[u];
+        }
+    };
 
-        if (active) {
-            // ---- S^T = K Q^T : two 32-key blocks
-            floatx16 s[2];
+    // ---- S^T = K Q^T for one 32-key block jb of a tile: s[qb], register r = key 32*jb + 8*(r/4) + 4*half + r%4
+    auto qk_block = [&](int stage, int jb, floatx16 (&s)[2]) {
+        const __bf16* kst = &Ksm[stage * TILE + 32 * jb * D];
 #pragma unroll
-            for (int jb = 0; jb < 2; ++jb) {
+        for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s[jb][r] = 0.f;
-                const __bf16* krow = &Ks[(32 * jb + l32) * KSTR + 8 * half];
+            for (int r = 0; r < 16; ++r) s[qb][r] = 0.f;
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 ka = *(const bf16x8*)(krow + 16 * ks);
-                    s[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks], s[jb], 0, 0, 0);
-                }
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 ka = *(const bf16x8*)(kst + koff[ks]);
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb)
+                s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[qb][ks], s[qb], 0, 0, 0);
+        }
+    };
+    auto mask_block = [&](int j0, floatx16 (&s)[2]) {
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int j = j0 + 8 * (r >> 2) + 4 * half + (r & 3);
+                // branch-free on purpose: one unsigned range test per segment
+                const bool ok = ((unsigned)j < (unsigned)n_text) | ((unsigned)(j - rs[qb].lo) <= rs[qb].span);
+                s[qb][r] = ok ? s[qb][r] : -INFINITY;
             }
-            // register r of block jb holds key j0 + 32*jb + 8*(r/4) + 4*half + r%4
-            if (masked) {
+    };
+    // ---- softmax of one 32-key block: weights as bf16 B operands pb[qb][tt], rescale factors alpha[qb].
+    // The online-softmax state advances once per block.
+    auto softmax_block = [&](floatx16 (&s)[2], bf16x8 (&pb)[2][2], float (&alpha)[2]) {
 #pragma unroll
-                for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int j = j0 + 32 * jb + 8 * (r >> 2) + 4 * half + (r & 3);
-                        // branch-free on purpose: one unsigned range test per segment
-                        const bool ok = ((unsigned)j < (unsigned)n_text) | ((unsigned)(j - lo) <= span);
-                        s[jb][r] = ok ? s[jb][r] : -INFINITY;
-                    }
-            }
-            // ---- online softmax (per-lane row statistics)
+        for (int qb = 0; qb < 2; ++qb) {
             float tmax = -INFINITY;
 #pragma unroll
-            for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[jb][r]);
-            tmax = fmaxf(tmax, xchg32(tmax));
-            const float m_new = fmaxf(m, tmax * c);
-            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-            m = m_new;
-            bf16x8 pb[2][2];
+            for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[qb][r]);
+            tmax = fmaxf(tmax, xchg32(tmax)) * c;
+            // The reference maximum only moves when it is exceeded by more than 2^kBump: weights
+            // stay <= 2^kBump (harmless in fp32 / bf16) and O is rescaled rarely.
+            const float m_old = rs[qb].m;
+            const float m_new = tmax > m_old + kBump ? tmax : m_old;
+            alpha[qb] = __builtin_amdgcn_exp2f(m_old - m_new);
+            rs[qb].m = m_new;
             float psum = 0.f;
+            bf16x2 ones;
+            ones[0] = (__bf16)1.0f;
+            ones[1] = (__bf16)1.0f;
 #pragma unroll
-            for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float pf = __builtin_amdgcn_exp2f(fmaf(s[jb][r], c, -m_new));
-                    const __bf16 pr = (__bf16)pf;           // the weight that enters P V ...
-                    pb[jb][r >> 3][r & 7] = pr;
-                    psum += (float)pr;                       // ... is also the one that is summed
-                }
-            l = l * alpha + psum;
+            for (int r = 0; r < 16; r += 2) {
+                floatx2 pf;
+                pf[0] = __builtin_amdgcn_exp2f(fmaf(s[qb][r], c, -m_new));
+                pf[1] = __builtin_amdgcn_exp2f(fmaf(s[qb][r + 1], c, -m_new));
+                const bf16x2 pr = __builtin_convertvector(pf, bf16x2);   // the weights that enter P V ...
+                pb[qb][r >> 3][r & 7] = pr[0];
+                pb[qb][r >> 3][(r & 7) + 1] = pr[1];
+                psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);   // ... are the ones summed
+            }
+            rs[qb].l = rs[qb].l * alpha[qb] + psum;
+        }
+    };
+    auto rescale = [&](const float (&alpha)[2]) {
+        // Uniform over the wavefront and rare: taken only when some row moved its reference maximum.
+        // The accumulators live in accumulation registers; they are scaled in place there so that the
+        // hot path never has to move them.  The waits cover MFMA results still in flight.
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(alpha[0] != 1.0f || alpha[1] != 1.0f) != 0, 0)) {
+            asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-            // ---- O^T += V^T P^T
+                for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                const __bf16* vrow = &Vt[(32 * db + l32) * VSTR + 4 * half];
-#pragma unroll
-                for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-                    for (int tt = 0; tt < 2; ++tt) {
-                        // k-slot e of this lane is key 32*jb + 16*tt + 4*half + (e<4 ? e : e+4)
-                        const bf16x4 v0 = *(const bf16x4*)(vrow + 32 * jb + 16 * tt);
-                        const bf16x4 v1 = *(const bf16x4*)(vrow + 32 * jb + 16 * tt + 8);
-                        const bf16x8 va = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-                        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[jb][tt], o[db], 0, 0, 0);
+                    for (int r = 0; r < 16; ++r) {
+                        float e = o[db][qb][r], t;
+                        asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\tv_accvgpr_write_b32 %0, %1"
+                                     : "+a"(e), "=&v"(t) : "v"(alpha[qb]));
+                        o[db][qb][r] = e;
                     }
-            }
+            asm volatile("s_nop 7" ::: "memory");
         }
-        __syncthreads();                  // every wavefront is done reading this tile
-        if (more) store_tile();
-        __syncthreads();
-    }
-
-    // ---- epilogue: O^T register r of block db is feature d = 32*db + 8*(r/4) + 4*half + r%4
-    const float l_tot = l + xchg32(l);
-    const float inv = 1.0f / l_tot;
-    if (i_raw < N) {
-        __bf16* orow = og + (int64_t)i_raw * a.stride_n;
+    };
+    // ---- O^T += V^T P^T for block jb; k-slot e of a lane is key 32*jb + 16*tt + 4*half + (e<4 ? e : e+4)
+    auto pv_block = [&](int stage, int jb, const bf16x8 (&pb)[2][2]) {
+        const __bf16* vst = &Vsm[stage * TILE + 32 * jb * D];
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                bf16x4 w4;
+            for (int tt = 0; tt < 2; ++tt) {
+                const __bf16* vp = vst + 16 * tt * D + voff[db];
+                const bf16x4 v0 = lds_read_tr16(vp);
+                const bf16x4 v1 = lds_read_tr16(vp + 8 * D);
+                const bf16x8 va = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) w4[e] = (__bf16)(o[db][4 * g + e] * inv);
-                *(bf16x4*)(orow + 32 * db + 8 * g + 4 * half) = w4;
+                for (int qb = 0; qb < 2; ++qb)
+                    o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[qb][tt], o[db][qb], 0, 0, 0);
             }
+    };
+
+    // ---- prologue: tiles 0 and 1 into the ring, S^T of block (tile 0, jb 0)
+    load_tile(tile_of(0));
+    store_tile(0);
+    load_tile(tile_of(1));
+    store_tile(1);
+    __syncthreads();
+
+    floatx16 s0[2], s1[2];                  // scores of the even / odd 32-key block in flight
+    qk_block(0, 0, s0);
+    if (tile_masked(0)) mask_block(tile_of(0) * kBN, s0);
+
+    // The pipeline advances by 32-key blocks.  Half-step A of tile idx: S^T of block (idx,1) next to
+    // the softmax of block (idx,0), then P V of block (idx,0).  Half-step B: S^T of block (idx+1,0)
+    // next to the softmax of block (idx,1), then P V of block (idx,1).  The body is kept free of
+    // alternatives (masks and rescales are small side blocks that modify registers in place) so that
+    // the accumulators keep one home for the whole loop.  In the last iteration block (idx+1,0) is a
+    // reload of the last tile whose scores are never used.
+    for (int idx = 0; idx < n_iter; ++idx) {
+        const int st_cur = idx % NST, st_nxt = (idx + 1) % NST, st_ld = (idx + 2) % NST;
+        __syncthreads();    // tile idx+1 is in LDS for everyone; stage st_ld is no longer read
+        load_tile(tile_of(idx + 2));
+        bf16x8 pb[2][2];
+        float alpha[2];
+        // ---- half-step A
+        qk_block(st_cur, 1, s1);
+        softmax_block(s0, pb, alpha);
+        if (__builtin_expect(tile_masked(idx), 0)) mask_block(tile_of(idx) * kBN + 32, s1);
+        rescale(alpha);
+        pv_block(st_cur, 0, pb);
+        // ---- half-step B
+        qk_block(st_nxt, 0, s0);
+        softmax_block(s1, pb, alpha);
+        if (__builtin_expect(tile_masked(idx + 1), 0)) mask_block(tile_of(idx + 1) * kBN, s0);
+        rescale(alpha);
+        pv_block(st_cur, 1, pb);
+        store_tile(st_ld);
+    }
+
+    // ---- epilogue: O^T register r of block db is feature d = 32*db + 8*(r/4) + 4*half + r%4
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        const float l_tot = rs[qb].l + xchg32(rs[qb].l);
+        const float inv = 1.0f / l_tot;
+        if (i_raw[qb] < N) {
+            __bf16* orow = og + (int64_t)i_raw[qb] * a.stride_n;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    bf16x4 w4;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) w4[e] = (__bf16)(o[db][qb][4 * g + e] * inv);
+                    *(bf16x4*)(orow + 32 * db + 8 * g + 4 * half) = w4;
+                }
+        }
     }
 }
 
@@ -265,8 +369,8 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a) {
     const float* __restrict__ vg = (const float*)a.v + base;
     float* __restrict__ og = (float*)a.out + base;
 
-    for (int r = 0; r < 32; ++r) {
-        const int i = it.q_tile * kBM + wave * 32 + r;
+    for (int r = 0; r < kBM / 4; ++r) {
+        const int i = it.q_tile * kBM + wave * (kBM / 4) + r;
         if (i >= N) break;                                   // uniform over the wavefront
         // allowed keys: [0, seg0_end) and [lo, hi]
         int seg0_end, lo, hi;

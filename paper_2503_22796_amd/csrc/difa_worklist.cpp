@@ -57,7 +57,7 @@ void mask_free_run(const Geometry& g, int w, int i0, int i1, int begin, int end,
 extern "C" int32_t difa_tile_shape(int32_t head_dim, int32_t dtype, int32_t* bm, int32_t* bn) {
     if ((head_dim != 64 && head_dim != 128) || (dtype != DIFA_DTYPE_BF16 && dtype != DIFA_DTYPE_F32))
         return 1;
-    if (bm) *bm = 128;
+    if (bm) *bm = 256;
     if (bn) *bn = 64;
     return 0;
 }
