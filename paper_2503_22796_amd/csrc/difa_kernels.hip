@@ -68,13 +68,14 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     constexpr int CPR = D / 8;              // 16-byte chunks per K/V row
     constexpr int LOADS = kBN * CPR / 256;  // 16-byte loads per thread per tensor per tile
     constexpr int TILE = kBN * D;           // elements of one K or V tile
-    constexpr int NST = 3;                  // LDS ring depth
+    constexpr int NSK = 3;                  // LDS ring depth for K tiles
+    constexpr int NSV = 4;                  // ... and for V tiles (P V trails S^T by one more block)
     constexpr float kBump = 8.0f;           // the reference maximum moves only when exceeded by 2^8
 
     // K rows: 16-byte chunk c of row r is stored at chunk c ^ (r % CPR)       (conflict-free b128 reads)
     // V rows: chunk c of row r is stored at chunk c ^ (2 * (r % 4))          (conflict-free transpose reads)
-    __shared__ __attribute__((aligned(16))) __bf16 Ksm[NST * TILE];
-    __shared__ __attribute__((aligned(16))) __bf16 Vsm[NST * TILE];
+    __shared__ __attribute__((aligned(16))) __bf16 Ksm[NSK * TILE];
+    __shared__ __attribute__((aligned(16))) __bf16 Vsm[NSV * TILE];
 
     const difa_work_item_t it = a.items[blockIdx.x];
     if (it.q_tile < 0) return;
@@ -166,19 +167,20 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
             vreg[u] = __builtin_amdgcn_raw_buffer_load_b128(vrsrc, goff[u] + tb, 0, 0);
         }
     };
-    auto store_tile = [&](int stage) {
+    auto store_tile = [&](int idx) {
+        const int ks = idx % NSK, vs = idx % NSV;
 #pragma unroll
         for (int u = 0; u < LOADS; ++u) {
             const int ch = tid + 256 * u;
             const int r = ch / CPR, cc = ch - r * CPR;
-            *(uintx4*)&Ksm[stage * TILE + r * D + 8 * (cc ^ (r & (CPR - 1)))] = kreg[u];
-            *(uintx4*)&Vsm[stage * TILE + r * D + 8 * (cc ^ (2 * (r & 3)))] = vreg[u];
+            *(uintx4*)&Ksm[ks * TILE + r * D + 8 * (cc ^ (r & (CPR - 1)))] = kreg[u];
+            *(uintx4*)&Vsm[vs * TILE + r * D + 8 * (cc ^ (2 * (r & 3)))] = vreg[u];
         }
     };
 
     // ---- S^T = K Q^T for one 32-key block jb of a tile: s[qb], register r = key 32*jb + 8*(r/4) + 4*half + r%4
-    auto qk_block = [&](int stage, int jb, floatx16 (&s)[2]) {
-        const __bf16* kst = &Ksm[stage * TILE + 32 * jb * D];
+    auto qk_block = [&](int idx, int jb, floatx16 (&s)[2]) {
+        const __bf16* kst = &Ksm[(idx % NSK) * TILE + 32 * jb * D];
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
@@ -202,36 +204,53 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
                 s[qb][r] = ok ? s[qb][r] : -INFINITY;
             }
     };
-    // ---- softmax of one 32-key block: weights as bf16 B operands pb[qb][tt], rescale factors alpha[qb].
+    // ---- softmax of one 32-key block, split in three pieces so that they can be laid between MFMAs.
+    //   sm_read : copy 8 scores of the block out of the accumulation registers, fold them into the
+    //             running block maximum
+    //   sm_stats: finish the block maximum across the two wavefront halves, move the reference
+    //             maximum if needed, produce the rescale factors
+    //   sm_exp  : weights of `cnt` consecutive score pairs as bf16 B operands + their sum
     // The online-softmax state advances once per block.
-    auto softmax_block = [&](floatx16 (&s)[2], bf16x8 (&pb)[2][2], float (&alpha)[2]) {
+    auto sm_read = [&](const floatx16 (&s)[2], float (&sv)[2][16], float (&tmax)[2], int part) {
+        const int qb = part >> 1, r0 = (part & 1) * 8;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) sv[qb][r0 + r] = s[qb][r0 + r];
+#pragma unroll
+        for (int r = 0; r < 8; r += 2) tmax[qb] = fmaxf(tmax[qb], fmaxf(sv[qb][r0 + r], sv[qb][r0 + r + 1]));
+    };
+    auto sm_stats = [&](float (&tmax)[2], float (&mneg)[2], float (&alpha)[2]) {
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
-            float tmax = -INFINITY;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[qb][r]);
-            tmax = fmaxf(tmax, xchg32(tmax)) * c;
+            const float t = fmaxf(tmax[qb], xchg32(tmax[qb])) * c;
             // The reference maximum only moves when it is exceeded by more than 2^kBump: weights
             // stay <= 2^kBump (harmless in fp32 / bf16) and O is rescaled rarely.
             const float m_old = rs[qb].m;
-            const float m_new = tmax > m_old + kBump ? tmax : m_old;
+            const float m_new = t > m_old + kBump ? t : m_old;
             alpha[qb] = __builtin_amdgcn_exp2f(m_old - m_new);
             rs[qb].m = m_new;
-            float psum = 0.f;
-            bf16x2 ones;
-            ones[0] = (__bf16)1.0f;
-            ones[1] = (__bf16)1.0f;
+            rs[qb].l *= alpha[qb];
+            mneg[qb] = -m_new;
+        }
+    };
+    auto sm_exp = [&](const float (&sv)[2][16], const float (&mneg)[2], bf16x8 (&pw)[2][2], int first_pair, int cnt) {
+        bf16x2 ones;
+        ones[0] = (__bf16)1.0f;
+        ones[1] = (__bf16)1.0f;
 #pragma unroll
-            for (int r = 0; r < 16; r += 2) {
-                floatx2 pf;
-                pf[0] = __builtin_amdgcn_exp2f(fmaf(s[qb][r], c, -m_new));
-                pf[1] = __builtin_amdgcn_exp2f(fmaf(s[qb][r + 1], c, -m_new));
-                const bf16x2 pr = __builtin_convertvector(pf, bf16x2);   // the weights that enter P V ...
-                pb[qb][r >> 3][r & 7] = pr[0];
-                pb[qb][r >> 3][(r & 7) + 1] = pr[1];
-                psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);   // ... are the ones summed
+        for (int pi = first_pair; pi < first_pair + cnt; ++pi) {   // pair pi: row block qb = pi/8, scores 2*(pi%8), +1
+            const int qb = pi >> 3, r = 2 * (pi & 7);
+            floatx2 pf;
+            pf[0] = __builtin_amdgcn_exp2f(fmaf(sv[qb][r], c, mneg[qb]));
+            pf[1] = __builtin_amdgcn_exp2f(fmaf(sv[qb][r + 1], c, mneg[qb]));
+            bf16x2 pr = __builtin_convertvector(pf, bf16x2);             // the weights that enter P V ...
+            {   // keep the computation in this slot: without the pin it is sunk to the block that uses it
+                unsigned bits = __builtin_bit_cast(unsigned, pr);
+                asm volatile("" : "+v"(bits));
+                pr = __builtin_bit_cast(bf16x2, bits);
             }
-            rs[qb].l = rs[qb].l * alpha[qb] + psum;
+            pw[qb][r >> 3][r & 7] = pr[0];
+            pw[qb][r >> 3][(r & 7) + 1] = pr[1];
+            rs[qb].l = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs[qb].l, false);   // ... are the ones summed
         }
     };
     auto rescale = [&](const float (&alpha)[2]) {
@@ -254,22 +273,17 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
             asm volatile("s_nop 7" ::: "memory");
         }
     };
-    // ---- O^T += V^T P^T for block jb; k-slot e of a lane is key 32*jb + 16*tt + 4*half + (e<4 ? e : e+4)
-    auto pv_block = [&](int stage, int jb, const bf16x8 (&pb)[2][2]) {
-        const __bf16* vst = &Vsm[stage * TILE + 32 * jb * D];
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int tt = 0; tt < 2; ++tt) {
-                const __bf16* vp = vst + 16 * tt * D + voff[db];
-                const bf16x4 v0 = lds_read_tr16(vp);
-                const bf16x4 v1 = lds_read_tr16(vp + 8 * D);
-                const bf16x8 va = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-#pragma unroll
-                for (int qb = 0; qb < 2; ++qb)
-                    o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[qb][tt], o[db][qb], 0, 0, 0);
-            }
+    // ---- O^T += V^T P^T: k-slot e of a lane is key 32*jb + 16*tt + 4*half + (e<4 ? e : e+4)
+    // ---- operand fetches from LDS
+    auto k_operand = [&](const __bf16* kst, int ks) { return *(const bf16x8*)(kst + koff[ks]); };
+    auto v_operand = [&](const __bf16* vst, int i) {          // operand i = 2*db + tt
+        const __bf16* vp = vst + 16 * (i & 1) * D + voff[i >> 1];
+        const bf16x4 v0 = lds_read_tr16(vp);
+        const bf16x4 v1 = lds_read_tr16(vp + 8 * D);
+        return (bf16x8)__builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
     };
+    auto k_block_ptr = [&](int idx, int jb) { return &Ksm[(idx % NSK) * TILE + 32 * jb * D]; };
+    auto v_block_ptr = [&](int idx, int jb) { return &Vsm[(idx % NSV) * TILE + 32 * jb * D]; };
 
     // ---- prologue: tiles 0 and 1 into the ring, S^T of block (tile 0, jb 0)
     load_tile(tile_of(0));
@@ -278,35 +292,96 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     store_tile(1);
     __syncthreads();
 
-    floatx16 s0[2], s1[2];                  // scores of the even / odd 32-key block in flight
+    // The pipeline advances by 32-key blocks g = 2*tile + jb.  One half-step for block g is
+    //   part 1:  P V of block g-1 (16 MFMA)  next to  the maximum / statistics of block g (VALU)
+    //   side  :  rescale of O if some row moved its reference maximum (rare)
+    //   part 2:  S^T of block g+1 (16 MFMA)  next to  the exponentials of block g (VALU)
+    //   side  :  element mask of the scores of block g+1 (edge tiles only)
+    // Every part is cut into 8 slots of 2 MFMAs that share one LDS operand; operands are fetched
+    // four slots ahead, and the slots are fenced so that the order written here is the order issued.
+    // K tiles live in a 3-deep ring, V tiles in a 4-deep ring because P V of a tile's second block
+    // runs one iteration after its S^T.  In the last iteration block g+1 is a reload of the last
+    // tile whose scores are never used.
+    constexpr int NOP = D / 16;             // LDS operands (= MFMA pairs) per part: 8 at D=128, 4 at D=64
+    constexpr int AHEAD = 4;                // operands fetched this many slots ahead
+    floatx16 s0[2], s1[2];                  // scores of the even / odd block in flight
+    bf16x8 pa[2][2], pb[2][2];              // weights of the even / odd block in flight
+    bf16x8 kq[NOP], vq[NOP];                // LDS operands in flight (slot i uses entry i)
+
+    auto half_step = [&](floatx16 (&s_cur)[2], floatx16 (&s_nxt)[2], const bf16x8 (&p_prev)[2][2],
+                         bf16x8 (&p_cur)[2][2], const __bf16* kst_nxt, const __bf16* vst_prev,
+                         const __bf16* vst_cur, bool with_pv, bool mask_nxt,
+                         int j0_nxt) __attribute__((always_inline)) {
+        float sv[2][16], tmax[2] = {-INFINITY, -INFINITY}, mneg[2], alpha[2];
+        // ---- part 1 (vq[0..AHEAD) were fetched by the previous half-step)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (with_pv && i < NOP) {
+                if (i + AHEAD < NOP) vq[i + AHEAD] = v_operand(vst_prev, i + AHEAD);
+#pragma unroll
+                for (int qb = 0; qb < 2; ++qb)
+                    o[i >> 1][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vq[i], p_prev[qb][i & 1], o[i >> 1][qb], 0, 0, 0);
+            }
+            if (i >= 8 - AHEAD) kq[i - (8 - AHEAD)] = k_operand(kst_nxt, i - (8 - AHEAD));
+            if (i < 4) sm_read(s_cur, sv, tmax, i);
+            if (i == 4) sm_stats(tmax, mneg, alpha);
+            if (i == 6) sm_exp(sv, mneg, p_cur, 0, 2);
+            if (i == 7) sm_exp(sv, mneg, p_cur, 2, 2);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (with_pv) rescale(alpha);
+        // ---- part 2
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s_nxt[qb][r] = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (i < NOP) {
+                if (i + AHEAD < NOP) kq[i + AHEAD] = k_operand(kst_nxt, i + AHEAD);
+#pragma unroll
+                for (int qb = 0; qb < 2; ++qb)
+                    s_nxt[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kq[i], qf[qb][i], s_nxt[qb], 0, 0, 0);
+            }
+            if (i >= 8 - AHEAD) vq[i - (8 - AHEAD)] = v_operand(vst_cur, i - (8 - AHEAD));
+            if (i < 4) sm_exp(sv, mneg, p_cur, 4 + 2 * i, 2); else sm_exp(sv, mneg, p_cur, 8 + i, 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (__builtin_expect(mask_nxt, 0)) mask_block(j0_nxt, s_nxt);
+    };
+    static_assert(NOP == 8 || NOP == 4, "slot layout assumes head_dim 128 or 64");
+    static_assert(AHEAD <= NOP, "operands are fetched at most one part ahead");
+
     qk_block(0, 0, s0);
     if (tile_masked(0)) mask_block(tile_of(0) * kBN, s0);
 
-    // The pipeline advances by 32-key blocks.  Half-step A of tile idx: S^T of block (idx,1) next to
-    // the softmax of block (idx,0), then P V of block (idx,0).  Half-step B: S^T of block (idx+1,0)
-    // next to the softmax of block (idx,1), then P V of block (idx,1).  The body is kept free of
-    // alternatives (masks and rescales are small side blocks that modify registers in place) so that
-    // the accumulators keep one home for the whole loop.  In the last iteration block (idx+1,0) is a
-    // reload of the last tile whose scores are never used.
-    for (int idx = 0; idx < n_iter; ++idx) {
-        const int st_cur = idx % NST, st_nxt = (idx + 1) % NST, st_ld = (idx + 2) % NST;
-        __syncthreads();    // tile idx+1 is in LDS for everyone; stage st_ld is no longer read
+    // first tile: its even block has no predecessor whose P V would be due
+    load_tile(tile_of(2));
+    half_step(s0, s1, pb, pa, k_block_ptr(0, 1), v_block_ptr(0, 0), v_block_ptr(0, 0), false,
+              tile_masked(0), tile_of(0) * kBN + 32);
+    half_step(s1, s0, pa, pb, k_block_ptr(1, 0), v_block_ptr(0, 0), v_block_ptr(0, 1), true,
+              tile_masked(1), tile_of(1) * kBN);
+    store_tile(2);
+
+    for (int idx = 1; idx < n_iter; ++idx) {
+        __syncthreads();    // tile idx+1 is in LDS for everyone; the stages of tile idx+2 are no longer read
         load_tile(tile_of(idx + 2));
-        bf16x8 pb[2][2];
-        float alpha[2];
-        // ---- half-step A
-        qk_block(st_cur, 1, s1);
-        softmax_block(s0, pb, alpha);
-        if (__builtin_expect(tile_masked(idx), 0)) mask_block(tile_of(idx) * kBN + 32, s1);
-        rescale(alpha);
-        pv_block(st_cur, 0, pb);
-        // ---- half-step B
-        qk_block(st_nxt, 0, s0);
-        softmax_block(s1, pb, alpha);
-        if (__builtin_expect(tile_masked(idx + 1), 0)) mask_block(tile_of(idx + 1) * kBN, s0);
-        rescale(alpha);
-        pv_block(st_cur, 1, pb);
-        store_tile(st_ld);
+        half_step(s0, s1, pb, pa, k_block_ptr(idx, 1), v_block_ptr(idx - 1, 1), v_block_ptr(idx, 0), true,
+                  tile_masked(idx), tile_of(idx) * kBN + 32);
+        half_step(s1, s0, pa, pb, k_block_ptr(idx + 1, 0), v_block_ptr(idx, 0), v_block_ptr(idx, 1), true,
+                  tile_masked(idx + 1), tile_of(idx + 1) * kBN);
+        store_tile(idx + 2);
+    }
+    // P V of the very last block (its operands 0..AHEAD-1 are already in flight)
+    {
+        const __bf16* vst = v_block_ptr(n_iter - 1, 1);
+#pragma unroll
+        for (int i = 0; i < NOP; ++i) {
+            if (i + AHEAD < NOP) vq[i + AHEAD] = v_operand(vst, i + AHEAD);
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb)
+                o[i >> 1][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vq[i], pb[qb][i & 1], o[i >> 1][qb], 0, 0, 0);
+        }
     }
 
     // ---- epilogue: O^T register r of block db is feature d = 32*db + 8*(r/4) + 4*half + r%4
