@@ -9,7 +9,7 @@ import os
 import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libdifa.so")
+LIB_PATH = os.environ.get("DIFA_LIBRARY", os.path.join(HERE, "libdifa.so"))   # override: another build of the same ABI
 
 DIFA_OK, DIFA_ERR_INVALID_ARG, DIFA_ERR_UNSUPPORTED, DIFA_ERR_ALLOC, DIFA_ERR_HIP = range(5)
 DIFA_HEAD_FULL, DIFA_HEAD_ARROW, DIFA_HEAD_CACHE = 0, 1, 2

@@ -13,9 +13,20 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-// Exchange between lane l and lane l^32 (the two halves of a wavefront).
-__device__ __forceinline__ float xchg32(float x) {
-    return __shfl_xor(x, 32, 64);
+// Maximum / sum of a value over the two halves of a wavefront (lanes l and l^32).
+// v_permlane32_swap is a VALU instruction: unlike ds_bpermute it does not queue behind the LDS
+// reads in flight.  With both operands equal it returns {low half, low half} and {high half, high half}.
+__device__ __forceinline__ float halves_max(float x) {
+    const unsigned u = __builtin_bit_cast(unsigned, x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    const unsigned lo = r[0], hi = r[1];    // copied to scalars first: a bit_cast applied directly to a vector element reads element 0
+    return fmaxf(__builtin_bit_cast(float, lo), __builtin_bit_cast(float, hi));
+}
+__device__ __forceinline__ float halves_sum(float x) {
+    const unsigned u = __builtin_bit_cast(unsigned, x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    const unsigned lo = r[0], hi = r[1];
+    return __builtin_bit_cast(float, lo) + __builtin_bit_cast(float, hi);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -66,10 +77,9 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     constexpr int KS = D / 16;              // MFMA k-steps of S^T = K Q^T
     constexpr int DB = D / 32;              // 32-row blocks of O^T
     constexpr int CPR = D / 8;              // 16-byte chunks per K/V row
-    constexpr int LOADS = kBN * CPR / 256;  // 16-byte loads per thread per tensor per tile
     constexpr int TILE = kBN * D;           // elements of one K or V tile
-    constexpr int NSK = 3;                  // LDS ring depth for K tiles
-    constexpr int NSV = 4;                  // ... and for V tiles (P V trails S^T by one more block)
+    constexpr int NSK = 4;                  // LDS ring depth for K tiles: two in use, one landed, one being loaded
+    constexpr int NSV = 5;                  // ... and for V tiles (P V trails S^T by one more block)
     constexpr float kBump = 8.0f;           // the reference maximum moves only when exceeded by 2^8
 
     // K rows: 16-byte chunk c of row r is stored at chunk c ^ (r % CPR)       (conflict-free b128 reads)
@@ -144,39 +154,55 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
         const int t = tile_of(idx);
         return idx < it.kv0_end ? (t >= it.nm0_end) : (t < it.nm1_begin || t >= it.nm1_end);
     };
-    // ---- global -> registers -> LDS staging of one K/V tile.  Buffer loads: one descriptor per
-    // tensor for this (batch, head), a per-thread byte offset that is constant over the loop plus the
-    // tile's byte offset; rows past the last token read as zero (they are masked later).
+    // ---- global -> LDS: K/V tiles are written into the ring by the load itself
+    // (buffer_load_dwordx4 ... lds: lane l of a wavefront deposits its 16 bytes at M0 + 16*l), so a
+    // tile never occupies registers and needs no ds_write.  One instruction fills RPI consecutive
+    // tile rows; the XOR swizzle of the LDS layout is applied by permuting which 16-byte chunk of the
+    // row each lane fetches.  One buffer descriptor per tensor for this (batch, head): rows past the
+    // last token read as zero (they are masked later).  The loads are outside the compiler's view, so
+    // the wait for them is explicit (dma_wait) and sits just before the barrier that publishes the tile.
+    constexpr int RPI = 64 / CPR;                           // tile rows per load instruction
+    constexpr int NDMA = kBN / RPI / 4;                     // load instructions per wavefront, tensor and tile
     const unsigned head_bytes = (unsigned)(((int64_t)(N - 1) * a.stride_n + D) * 2);
-    const __amdgpu_buffer_rsrc_t krsrc = __builtin_amdgcn_make_buffer_rsrc((void*)kg, 0, head_bytes, 0x00020000);
-    const __amdgpu_buffer_rsrc_t vrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)vg, 0, head_bytes, 0x00020000);
-    unsigned goff[LOADS];
+    uintx4 krsrc, vrsrc;
+    {
+        const unsigned long long ka = (unsigned long long)kg, va = (unsigned long long)vg;
+        krsrc[0] = (unsigned)ka; krsrc[1] = (unsigned)(ka >> 32) & 0xffffu; krsrc[2] = head_bytes; krsrc[3] = 0x00020000u;
+        vrsrc[0] = (unsigned)va; vrsrc[1] = (unsigned)(va >> 32) & 0xffffu; vrsrc[2] = head_bytes; vrsrc[3] = 0x00020000u;
+    }
+    const unsigned wave_u = __builtin_amdgcn_readfirstlane(wave);
+    unsigned gk[NDMA], gv[NDMA];                            // per-lane byte offsets inside a tile
 #pragma unroll
-    for (int u = 0; u < LOADS; ++u) {
-        const int ch = tid + 256 * u;
-        const int r = ch / CPR, cc = ch - r * CPR;
-        goff[u] = (unsigned)(r * (int)a.stride_n + 8 * cc) * 2u;
+    for (int u = 0; u < NDMA; ++u) {
+        const int r = (wave * NDMA + u) * RPI + lane / CPR, pc = lane % CPR;   // tile row, chunk slot in LDS
+        gk[u] = (unsigned)(r * (int)a.stride_n + 8 * (pc ^ (r & (CPR - 1)))) * 2u;
+        gv[u] = (unsigned)(r * (int)a.stride_n + 8 * (pc ^ (2 * (r & 3)))) * 2u;
     }
     const unsigned tile_bytes = (unsigned)(kBN * (int)a.stride_n) * 2u;
-    uintx4 kreg[LOADS], vreg[LOADS];
-    auto load_tile = [&](int t) {
-        const unsigned tb = (unsigned)t * tile_bytes;
-#pragma unroll
-        for (int u = 0; u < LOADS; ++u) {
-            kreg[u] = __builtin_amdgcn_raw_buffer_load_b128(krsrc, goff[u] + tb, 0, 0);
-            vreg[u] = __builtin_amdgcn_raw_buffer_load_b128(vrsrc, goff[u] + tb, 0, 0);
+    const unsigned k_lds = (unsigned)(unsigned long long)(__attribute__((address_space(3))) __bf16*)Ksm;
+    const unsigned v_lds = (unsigned)(unsigned long long)(__attribute__((address_space(3))) __bf16*)Vsm;
+    // One load instruction: part u (0..NDMA-1) of the K (tensor 0) or V (tensor 1) tile at position idx of
+    // the work record's tile sequence.  Positions past the end are given an offset beyond the buffer:
+    // they fetch nothing and deposit zeros.
+    auto dma_part = [&](int idx, int tensor, int u) __attribute__((always_inline)) {
+        const unsigned tb = idx < n_iter ? (unsigned)tile_of(idx) * tile_bytes : 0x80000000u;
+        if (tensor == 0) {
+            const unsigned kd = k_lds + (unsigned)(((idx % NSK) * TILE + (wave_u * NDMA + u) * RPI * D) * 2);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                         :: "s"(kd), "v"(gk[u] + tb), "s"(krsrc));
+        } else {
+            const unsigned vd = v_lds + (unsigned)(((idx % NSV) * TILE + (wave_u * NDMA + u) * RPI * D) * 2);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                         :: "s"(vd), "v"(gv[u] + tb), "s"(vrsrc));
         }
     };
-    auto store_tile = [&](int idx) {
-        const int ks = idx % NSK, vs = idx % NSV;
+    auto dma_tile = [&](int idx) {
 #pragma unroll
-        for (int u = 0; u < LOADS; ++u) {
-            const int ch = tid + 256 * u;
-            const int r = ch / CPR, cc = ch - r * CPR;
-            *(uintx4*)&Ksm[ks * TILE + r * D + 8 * (cc ^ (r & (CPR - 1)))] = kreg[u];
-            *(uintx4*)&Vsm[vs * TILE + r * D + 8 * (cc ^ (2 * (r & 3)))] = vreg[u];
-        }
+        for (int u = 0; u < NDMA; ++u) { dma_part(idx, 0, u); dma_part(idx, 1, u); }
     };
+    // all loads done / all but the 2*NDMA youngest (= the tile issued during the current iteration) done
+    auto dma_wait_all = [] { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
+    auto dma_wait_older = [] { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * NDMA) : "memory"); };
 
     // ---- S^T = K Q^T for one 32-key block jb of a tile: s[qb], register r = key 32*jb + 8*(r/4) + 4*half + r%4
     auto qk_block = [&](int idx, int jb, floatx16 (&s)[2]) {
@@ -204,24 +230,28 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
                 s[qb][r] = ok ? s[qb][r] : -INFINITY;
             }
     };
-    // ---- softmax of one 32-key block, split in three pieces so that they can be laid between MFMAs.
-    //   sm_read : copy 8 scores of the block out of the accumulation registers, fold them into the
-    //             running block maximum
-    //   sm_stats: finish the block maximum across the two wavefront halves, move the reference
-    //             maximum if needed, produce the rescale factors
-    //   sm_exp  : weights of `cnt` consecutive score pairs as bf16 B operands + their sum
-    // The online-softmax state advances once per block.
-    auto sm_read = [&](const floatx16 (&s)[2], float (&sv)[2][16], float (&tmax)[2], int part) {
-        const int qb = part >> 1, r0 = (part & 1) * 8;
+    // ---- softmax of one 32-key block, cut into 32 small VALU pieces that are laid between MFMAs
+    // (a wavefront's own VALU work hides behind its MFMAs only in the few cycles after each issue).
+    //   pieces 0..7  : copy 4 scores of the block out of the accumulators, fold them into the block maximum
+    //   pieces 8, 9  : finish the maximum across the two wavefront halves, move the reference maximum if
+    //                  needed, produce the rescale factor (one row block each)
+    //   pieces 12..27: one score pair each -> two weights as bf16 B operands, added to the row sum
+    // Each piece ends in an empty volatile asm on its results: that keeps it in its slot (otherwise the
+    // optimizer sinks the arithmetic to the block that uses it).  The online-softmax state advances
+    // once per block.
+    auto pin = [](float& x) { asm volatile("" : "+v"(x)); };
+    auto softmax_piece = [&](int h, const floatx16 (&sc)[2], float (&sv)[2][16], float (&tmax)[2],
+                             float (&mneg)[2], float (&alpha)[2], bf16x8 (&pw)[2][2]) __attribute__((always_inline)) {
+        if (h < 8) {
+            const int qb = h >> 2, r0 = (h & 3) * 4;
 #pragma unroll
-        for (int r = 0; r < 8; ++r) sv[qb][r0 + r] = s[qb][r0 + r];
-#pragma unroll
-        for (int r = 0; r < 8; r += 2) tmax[qb] = fmaxf(tmax[qb], fmaxf(sv[qb][r0 + r], sv[qb][r0 + r + 1]));
-    };
-    auto sm_stats = [&](float (&tmax)[2], float (&mneg)[2], float (&alpha)[2]) {
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            const float t = fmaxf(tmax[qb], xchg32(tmax[qb])) * c;
+            for (int r = 0; r < 4; ++r) sv[qb][r0 + r] = sc[qb][r0 + r];
+            tmax[qb] = fmaxf(fmaxf(tmax[qb], sv[qb][r0]), sv[qb][r0 + 1]);
+            tmax[qb] = fmaxf(fmaxf(tmax[qb], sv[qb][r0 + 2]), sv[qb][r0 + 3]);
+            pin(tmax[qb]);
+        } else if (h < 10) {
+            const int qb = h - 8;
+            const float t = halves_max(tmax[qb]) * c;
             // The reference maximum only moves when it is exceeded by more than 2^kBump: weights
             // stay <= 2^kBump (harmless in fp32 / bf16) and O is rescaled rarely.
             const float m_old = rs[qb].m;
@@ -230,27 +260,24 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
             rs[qb].m = m_new;
             rs[qb].l *= alpha[qb];
             mneg[qb] = -m_new;
-        }
-    };
-    auto sm_exp = [&](const float (&sv)[2][16], const float (&mneg)[2], bf16x8 (&pw)[2][2], int first_pair, int cnt) {
-        bf16x2 ones;
-        ones[0] = (__bf16)1.0f;
-        ones[1] = (__bf16)1.0f;
-#pragma unroll
-        for (int pi = first_pair; pi < first_pair + cnt; ++pi) {   // pair pi: row block qb = pi/8, scores 2*(pi%8), +1
-            const int qb = pi >> 3, r = 2 * (pi & 7);
+            pin(mneg[qb]);
+            pin(alpha[qb]);
+        } else if (h >= 12 && h < 28) {
+            const int pi = h - 12, qb = pi >> 3, r = 2 * (pi & 7);
+            bf16x2 ones;
+            ones[0] = (__bf16)1.0f;
+            ones[1] = (__bf16)1.0f;
             floatx2 pf;
             pf[0] = __builtin_amdgcn_exp2f(fmaf(sv[qb][r], c, mneg[qb]));
             pf[1] = __builtin_amdgcn_exp2f(fmaf(sv[qb][r + 1], c, mneg[qb]));
             bf16x2 pr = __builtin_convertvector(pf, bf16x2);             // the weights that enter P V ...
-            {   // keep the computation in this slot: without the pin it is sunk to the block that uses it
-                unsigned bits = __builtin_bit_cast(unsigned, pr);
-                asm volatile("" : "+v"(bits));
-                pr = __builtin_bit_cast(bf16x2, bits);
-            }
+            unsigned bits = __builtin_bit_cast(unsigned, pr);
+            asm volatile("" : "+v"(bits));
+            pr = __builtin_bit_cast(bf16x2, bits);
             pw[qb][r >> 3][r & 7] = pr[0];
             pw[qb][r >> 3][(r & 7) + 1] = pr[1];
             rs[qb].l = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs[qb].l, false);   // ... are the ones summed
+            pin(rs[qb].l);
         }
     };
     auto rescale = [&](const float (&alpha)[2]) {
@@ -286,93 +313,92 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     auto v_block_ptr = [&](int idx, int jb) { return &Vsm[(idx % NSV) * TILE + 32 * jb * D]; };
 
     // ---- prologue: tiles 0 and 1 into the ring, S^T of block (tile 0, jb 0)
-    load_tile(tile_of(0));
-    store_tile(0);
-    load_tile(tile_of(1));
-    store_tile(1);
+    dma_tile(0);
+    dma_tile(1);
+    dma_tile(2);
+    dma_wait_all();
     __syncthreads();
 
-    // The pipeline advances by 32-key blocks g = 2*tile + jb.  One half-step for block g is
-    //   part 1:  P V of block g-1 (16 MFMA)  next to  the maximum / statistics of block g (VALU)
-    //   side  :  rescale of O if some row moved its reference maximum (rare)
-    //   part 2:  S^T of block g+1 (16 MFMA)  next to  the exponentials of block g (VALU)
-    //   side  :  element mask of the scores of block g+1 (edge tiles only)
-    // Every part is cut into 8 slots of 2 MFMAs that share one LDS operand; operands are fetched
-    // four slots ahead, and the slots are fenced so that the order written here is the order issued.
-    // K tiles live in a 3-deep ring, V tiles in a 4-deep ring because P V of a tile's second block
-    // runs one iteration after its S^T.  In the last iteration block g+1 is a reload of the last
-    // tile whose scores are never used.
-    constexpr int NOP = D / 16;             // LDS operands (= MFMA pairs) per part: 8 at D=128, 4 at D=64
-    constexpr int AHEAD = 4;                // operands fetched this many slots ahead
+    // The pipeline advances by 32-key blocks g = 2*tile + jb.  One half-step for block g is one basic
+    // block of 16 slots; slot s issues
+    //     MFMA s of S^T of block g+1   | two pieces of the softmax of block g |   MFMA s of P V of block g-1
+    // so that consecutive MFMAs never depend on each other and every MFMA has a few VALU
+    // instructions behind it.  LDS operands are fetched three operands (six slots) ahead, across
+    // half-step boundaries.  Two rare side blocks follow and modify registers in place: the rescale
+    // of O by the factors the softmax just produced (after P V of block g-1, before P V of block g)
+    // and the element mask of the scores of block g+1.  K tiles live in a 3-deep ring, V tiles in a
+    // 4-deep ring because P V of a tile's second block runs one iteration after its S^T.  In the
+    // last iteration block g+1 is a reload of the last tile whose scores are never used.
+    constexpr int NOP = D / 16;             // LDS operands per MFMA stream per half-step: 8 at D=128, 4 at D=64
+    constexpr int NMF = 2 * NOP;            // MFMAs per stream per half-step
+    constexpr int AHEAD = 3;                // operands in flight per stream
+    static_assert(NOP == 8 || NOP == 4, "slot layout assumes head_dim 128 or 64");
     floatx16 s0[2], s1[2];                  // scores of the even / odd block in flight
     bf16x8 pa[2][2], pb[2][2];              // weights of the even / odd block in flight
-    bf16x8 kq[NOP], vq[NOP];                // LDS operands in flight (slot i uses entry i)
+    bf16x8 kq[NOP], vq[NOP];                // LDS operands (entry j = operand j of the stream)
 
-    auto half_step = [&](floatx16 (&s_cur)[2], floatx16 (&s_nxt)[2], const bf16x8 (&p_prev)[2][2],
-                         bf16x8 (&p_cur)[2][2], const __bf16* kst_nxt, const __bf16* vst_prev,
-                         const __bf16* vst_cur, bool with_pv, bool mask_nxt,
-                         int j0_nxt) __attribute__((always_inline)) {
+    auto half_step = [&](const floatx16 (&s_cur)[2], floatx16 (&s_nxt)[2], const bf16x8 (&p_prev)[2][2],
+                         bf16x8 (&p_cur)[2][2], const __bf16* kst_nxt, const __bf16* kst_after,
+                         const __bf16* vst_prev, const __bf16* vst_cur, bool with_pv, bool mask_nxt,
+                         int j0_nxt, int dma_idx, int dma_tensor) __attribute__((always_inline)) {
         float sv[2][16], tmax[2] = {-INFINITY, -INFINITY}, mneg[2], alpha[2];
-        // ---- part 1 (vq[0..AHEAD) were fetched by the previous half-step)
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            if (with_pv && i < NOP) {
-                if (i + AHEAD < NOP) vq[i + AHEAD] = v_operand(vst_prev, i + AHEAD);
-#pragma unroll
-                for (int qb = 0; qb < 2; ++qb)
-                    o[i >> 1][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vq[i], p_prev[qb][i & 1], o[i >> 1][qb], 0, 0, 0);
-            }
-            if (i >= 8 - AHEAD) kq[i - (8 - AHEAD)] = k_operand(kst_nxt, i - (8 - AHEAD));
-            if (i < 4) sm_read(s_cur, sv, tmax, i);
-            if (i == 4) sm_stats(tmax, mneg, alpha);
-            if (i == 6) sm_exp(sv, mneg, p_cur, 0, 2);
-            if (i == 7) sm_exp(sv, mneg, p_cur, 2, 2);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if (with_pv) rescale(alpha);
-        // ---- part 2
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) s_nxt[qb][r] = 0.f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            if (i < NOP) {
-                if (i + AHEAD < NOP) kq[i + AHEAD] = k_operand(kst_nxt, i + AHEAD);
-#pragma unroll
-                for (int qb = 0; qb < 2; ++qb)
-                    s_nxt[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kq[i], qf[qb][i], s_nxt[qb], 0, 0, 0);
+        for (int s = 0; s < 16; ++s) {
+            const int j = s >> 1, qb = s & 1;
+            if (s < NMF) {
+                if (qb == 0) {      // fetch operand j+AHEAD: of this half-step, or of the next one
+                    const int jn = j + AHEAD;
+                    if (jn < NOP) {
+                        kq[jn] = k_operand(kst_nxt, jn);
+                        if (with_pv) vq[jn] = v_operand(vst_prev, jn);
+                    } else {
+                        kq[jn - NOP] = k_operand(kst_after, jn - NOP);
+                        vq[jn - NOP] = v_operand(vst_cur, jn - NOP);
+                    }
+                }
+                s_nxt[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kq[j], qf[qb][j], s_nxt[qb], 0, 0, 0);
             }
-            if (i >= 8 - AHEAD) vq[i - (8 - AHEAD)] = v_operand(vst_cur, i - (8 - AHEAD));
-            if (i < 4) sm_exp(sv, mneg, p_cur, 4 + 2 * i, 2); else sm_exp(sv, mneg, p_cur, 8 + i, 1);
+            softmax_piece(2 * s, s_cur, sv, tmax, mneg, alpha, p_cur);
+            if (with_pv && s < NMF)
+                o[j >> 1][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vq[j], p_prev[qb][j & 1], o[j >> 1][qb], 0, 0, 0);
+            softmax_piece(2 * s + 1, s_cur, sv, tmax, mneg, alpha, p_cur);
+            // the loads of the tile three positions ahead are spread over the slots (a burst of them
+            // right after the barrier stalls all four wavefronts on the one memory pipe)
+            if ((s & 3) == 1 && (s >> 2) < NDMA) dma_part(dma_idx, dma_tensor, s >> 2);
             __builtin_amdgcn_sched_barrier(0);
         }
+        if (with_pv) rescale(alpha);
         if (__builtin_expect(mask_nxt, 0)) mask_block(j0_nxt, s_nxt);
     };
-    static_assert(NOP == 8 || NOP == 4, "slot layout assumes head_dim 128 or 64");
-    static_assert(AHEAD <= NOP, "operands are fetched at most one part ahead");
 
     qk_block(0, 0, s0);
     if (tile_masked(0)) mask_block(tile_of(0) * kBN, s0);
 
     // first tile: its even block has no predecessor whose P V would be due
-    load_tile(tile_of(2));
-    half_step(s0, s1, pb, pa, k_block_ptr(0, 1), v_block_ptr(0, 0), v_block_ptr(0, 0), false,
-              tile_masked(0), tile_of(0) * kBN + 32);
-    half_step(s1, s0, pa, pb, k_block_ptr(1, 0), v_block_ptr(0, 0), v_block_ptr(0, 1), true,
-              tile_masked(1), tile_of(1) * kBN);
-    store_tile(2);
+#pragma unroll
+    for (int j = 0; j < AHEAD; ++j) kq[j] = k_operand(k_block_ptr(0, 1), j);
+    half_step(s0, s1, pb, pa, k_block_ptr(0, 1), k_block_ptr(1, 0), v_block_ptr(0, 0), v_block_ptr(0, 0), false,
+              tile_masked(0), tile_of(0) * kBN + 32, 3, 0);
+    half_step(s1, s0, pa, pb, k_block_ptr(1, 0), k_block_ptr(1, 1), v_block_ptr(0, 0), v_block_ptr(0, 1), true,
+              tile_masked(1), tile_of(1) * kBN, 3, 1);
+    dma_wait_older();
 
+    // Iteration idx works on tiles idx-1 (P V), idx and idx+1 (S^T), issues the loads of tile idx+3 and,
+    // before the next barrier, waits for the loads of tile idx+2 (issued one iteration earlier).
     for (int idx = 1; idx < n_iter; ++idx) {
-        __syncthreads();    // tile idx+1 is in LDS for everyone; the stages of tile idx+2 are no longer read
-        load_tile(tile_of(idx + 2));
-        half_step(s0, s1, pb, pa, k_block_ptr(idx, 1), v_block_ptr(idx - 1, 1), v_block_ptr(idx, 0), true,
-                  tile_masked(idx), tile_of(idx) * kBN + 32);
-        half_step(s1, s0, pa, pb, k_block_ptr(idx + 1, 0), v_block_ptr(idx, 0), v_block_ptr(idx, 1), true,
-                  tile_masked(idx + 1), tile_of(idx + 1) * kBN);
-        store_tile(idx + 2);
+        __syncthreads();    // tile idx+1 is in LDS for everyone; the stages of tile idx+3 are no longer read
+        half_step(s0, s1, pb, pa, k_block_ptr(idx, 1), k_block_ptr(idx + 1, 0), v_block_ptr(idx - 1, 1),
+                  v_block_ptr(idx, 0), true, tile_masked(idx), tile_of(idx) * kBN + 32, idx + 3, 0);
+        half_step(s1, s0, pa, pb, k_block_ptr(idx + 1, 0), k_block_ptr(idx + 1, 1), v_block_ptr(idx, 0),
+                  v_block_ptr(idx, 1), true, tile_masked(idx + 1), tile_of(idx + 1) * kBN, idx + 3, 1);
+        dma_wait_older();
     }
-    // P V of the very last block (its operands 0..AHEAD-1 are already in flight)
+    dma_wait_all();     // nothing may still be landing in LDS when the wavefront ends
+    // P V of the very last block (its first operands are already in flight)
     {
         const __bf16* vst = v_block_ptr(n_iter - 1, 1);
 #pragma unroll
@@ -387,7 +413,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     // ---- epilogue: O^T register r of block db is feature d = 32*db + 8*(r/4) + 4*half + r%4
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-        const float l_tot = rs[qb].l + xchg32(rs[qb].l);
+        const float l_tot = halves_sum(rs[qb].l);
         const float inv = 1.0f / l_tot;
         if (i_raw[qb] < N) {
             __bf16* orow = og + (int64_t)i_raw[qb] * a.stride_n;
