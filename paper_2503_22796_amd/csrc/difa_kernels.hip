@@ -181,24 +181,28 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     const unsigned tile_bytes = (unsigned)(kBN * (int)a.stride_n) * 2u;
     const unsigned k_lds = (unsigned)(unsigned long long)(__attribute__((address_space(3))) __bf16*)Ksm;
     const unsigned v_lds = (unsigned)(unsigned long long)(__attribute__((address_space(3))) __bf16*)Vsm;
-    // One load instruction: part u (0..NDMA-1) of the K (tensor 0) or V (tensor 1) tile at position idx of
-    // the work record's tile sequence.  Positions past the end are given an offset beyond the buffer:
-    // they fetch nothing and deposit zeros.
-    auto dma_part = [&](int idx, int tensor, int u) __attribute__((always_inline)) {
-        const unsigned tb = idx < n_iter ? (unsigned)tile_of(idx) * tile_bytes : 0x80000000u;
-        if (tensor == 0) {
-            const unsigned kd = k_lds + (unsigned)(((idx % NSK) * TILE + (wave_u * NDMA + u) * RPI * D) * 2);
+    // One load instruction: part u (0..NDMA-1) of a K (tensor 0) or V (tensor 1) tile.  `tb` is the tile's
+    // byte offset inside the head, or an offset beyond the buffer for positions past the end of the
+    // record (those fetch nothing and deposit zeros); `dst` is this wavefront's LDS byte address inside
+    // the ring stage.  All per-tile scalars are computed once per iteration by the caller.
+    auto dma_part = [&](int tensor, int u, unsigned tb, unsigned dst) __attribute__((always_inline)) {
+        if (tensor == 0)
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                         :: "s"(kd), "v"(gk[u] + tb), "s"(krsrc));
-        } else {
-            const unsigned vd = v_lds + (unsigned)(((idx % NSV) * TILE + (wave_u * NDMA + u) * RPI * D) * 2);
+                         :: "s"(dst + (unsigned)(u * RPI * D * 2)), "v"(gk[u] + tb), "s"(krsrc));
+        else
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                         :: "s"(vd), "v"(gv[u] + tb), "s"(vrsrc));
-        }
+                         :: "s"(dst + (unsigned)(u * RPI * D * 2)), "v"(gv[u] + tb), "s"(vrsrc));
+    };
+    const unsigned wave_lds = wave_u * (unsigned)(NDMA * RPI * D * 2);     // this wavefront's rows inside a stage
+    auto tile_offset = [&](int idx) {                       // byte offset of the tile at position idx
+        return idx < n_iter ? (unsigned)tile_of(idx) * tile_bytes : 0x80000000u;
     };
     auto dma_tile = [&](int idx) {
+        const unsigned tb = tile_offset(idx);
+        const unsigned kd = k_lds + (unsigned)((idx % NSK) * TILE * 2) + wave_lds;
+        const unsigned vd = v_lds + (unsigned)((idx % NSV) * TILE * 2) + wave_lds;
 #pragma unroll
-        for (int u = 0; u < NDMA; ++u) { dma_part(idx, 0, u); dma_part(idx, 1, u); }
+        for (int u = 0; u < NDMA; ++u) { dma_part(0, u, tb, kd); dma_part(1, u, tb, vd); }
     };
     // all loads done / all but the 2*NDMA youngest (= the tile issued during the current iteration) done
     auto dma_wait_all = [] { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
@@ -309,8 +313,6 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
         const bf16x4 v1 = lds_read_tr16(vp + 8 * D);
         return (bf16x8)__builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
     };
-    auto k_block_ptr = [&](int idx, int jb) { return &Ksm[(idx % NSK) * TILE + 32 * jb * D]; };
-    auto v_block_ptr = [&](int idx, int jb) { return &Vsm[(idx % NSV) * TILE + 32 * jb * D]; };
 
     // ---- prologue: tiles 0 and 1 into the ring, S^T of block (tile 0, jb 0)
     dma_tile(0);
@@ -340,7 +342,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     auto half_step = [&](const floatx16 (&s_cur)[2], floatx16 (&s_nxt)[2], const bf16x8 (&p_prev)[2][2],
                          bf16x8 (&p_cur)[2][2], const __bf16* kst_nxt, const __bf16* kst_after,
                          const __bf16* vst_prev, const __bf16* vst_cur, bool with_pv, bool mask_nxt,
-                         int j0_nxt, int dma_idx, int dma_tensor) __attribute__((always_inline)) {
+                         int blk_nxt, int dma_tensor, unsigned dma_tb, unsigned dma_dst) __attribute__((always_inline)) {
         float sv[2][16], tmax[2] = {-INFINITY, -INFINITY}, mneg[2], alpha[2];
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb)
@@ -368,39 +370,62 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
             softmax_piece(2 * s + 1, s_cur, sv, tmax, mneg, alpha, p_cur);
             // the loads of the tile three positions ahead are spread over the slots (a burst of them
             // right after the barrier stalls all four wavefronts on the one memory pipe)
-            if ((s & 3) == 1 && (s >> 2) < NDMA) dma_part(dma_idx, dma_tensor, s >> 2);
+            if ((s & 3) == 1 && (s >> 2) < NDMA) dma_part(dma_tensor, s >> 2, dma_tb, dma_dst);
             __builtin_amdgcn_sched_barrier(0);
         }
         if (with_pv) rescale(alpha);
-        if (__builtin_expect(mask_nxt, 0)) mask_block(j0_nxt, s_nxt);
+        // block number blk_nxt = 2*position + jb; its first key is only needed on this rare path
+        if (__builtin_expect(mask_nxt, 0)) mask_block(tile_of(blk_nxt >> 1) * kBN + 32 * (blk_nxt & 1), s_nxt);
     };
 
     qk_block(0, 0, s0);
-    if (tile_masked(0)) mask_block(tile_of(0) * kBN, s0);
+    if (tile_masked(0)) mask_block(tile_of(0) * kBN, s0);   // (before the loop-carried flags exist)
+
+    // Loop-carried scalars (all uniform over the wavefront), advanced once per iteration instead of
+    // being recomputed from the position: ring stages of the tiles in use, mask flags, load target.
+    // With one wavefront per SIMD nothing hides scalar work, so there is as little of it as possible.
+    const int m0e = it.nm0_end < it.kv0_end ? it.nm0_end : it.kv0_end;          // positions [0, m0e) and
+    const int m1b = it.kv0_end + (it.nm1_begin > it.kv1_begin ? it.nm1_begin - it.kv1_begin : 0);
+    const int m1e = it.kv0_end + ((it.nm1_end < it.kv1_end ? it.nm1_end : it.kv1_end) - it.kv1_begin);
+    auto pos_masked = [&](int idx) { return !(idx < m0e || (idx >= m1b && idx < m1e)); };   // [m1b, m1e) are mask-free
+    auto bump = [](int& st, int n) { st = st + 1 == n ? 0 : st + 1; };
+    auto kptr = [&](int st, int jb) { return &Ksm[st * TILE + 32 * jb * D]; };
+    auto vptr = [&](int st, int jb) { return &Vsm[st * TILE + 32 * jb * D]; };
+    int k_cur = 0, k_nxt = 1, k_ld = 3 % NSK;               // K stages of positions idx, idx+1, idx+3
+    int v_prv = 0, v_cur = 0, v_ld = 3 % NSV;               // V stages of positions idx-1, idx, idx+3
+    bool msk_cur = pos_masked(0), msk_nxt = pos_masked(1);
 
     // first tile: its even block has no predecessor whose P V would be due
 #pragma unroll
-    for (int j = 0; j < AHEAD; ++j) kq[j] = k_operand(k_block_ptr(0, 1), j);
-    half_step(s0, s1, pb, pa, k_block_ptr(0, 1), k_block_ptr(1, 0), v_block_ptr(0, 0), v_block_ptr(0, 0), false,
-              tile_masked(0), tile_of(0) * kBN + 32, 3, 0);
-    half_step(s1, s0, pa, pb, k_block_ptr(1, 0), k_block_ptr(1, 1), v_block_ptr(0, 0), v_block_ptr(0, 1), true,
-              tile_masked(1), tile_of(1) * kBN, 3, 1);
+    for (int j = 0; j < AHEAD; ++j) kq[j] = k_operand(kptr(k_cur, 1), j);
+    {
+        const unsigned tb = tile_offset(3);
+        half_step(s0, s1, pb, pa, kptr(k_cur, 1), kptr(k_nxt, 0), vptr(v_cur, 0), vptr(v_cur, 0), false,
+                  msk_cur, 1, 0, tb, k_lds + (unsigned)(k_ld * TILE * 2) + wave_lds);
+        half_step(s1, s0, pa, pb, kptr(k_nxt, 0), kptr(k_nxt, 1), vptr(v_cur, 0), vptr(v_cur, 1), true,
+                  msk_nxt, 2, 1, tb, v_lds + (unsigned)(v_ld * TILE * 2) + wave_lds);
+    }
     dma_wait_older();
 
     // Iteration idx works on tiles idx-1 (P V), idx and idx+1 (S^T), issues the loads of tile idx+3 and,
     // before the next barrier, waits for the loads of tile idx+2 (issued one iteration earlier).
     for (int idx = 1; idx < n_iter; ++idx) {
+        v_prv = v_cur;
+        bump(k_cur, NSK); bump(k_nxt, NSK); bump(k_ld, NSK); bump(v_cur, NSV); bump(v_ld, NSV);
+        msk_cur = msk_nxt;
+        msk_nxt = pos_masked(idx + 1);
+        const unsigned tb = tile_offset(idx + 3);
         __syncthreads();    // tile idx+1 is in LDS for everyone; the stages of tile idx+3 are no longer read
-        half_step(s0, s1, pb, pa, k_block_ptr(idx, 1), k_block_ptr(idx + 1, 0), v_block_ptr(idx - 1, 1),
-                  v_block_ptr(idx, 0), true, tile_masked(idx), tile_of(idx) * kBN + 32, idx + 3, 0);
-        half_step(s1, s0, pa, pb, k_block_ptr(idx + 1, 0), k_block_ptr(idx + 1, 1), v_block_ptr(idx, 0),
-                  v_block_ptr(idx, 1), true, tile_masked(idx + 1), tile_of(idx + 1) * kBN, idx + 3, 1);
+        half_step(s0, s1, pb, pa, kptr(k_cur, 1), kptr(k_nxt, 0), vptr(v_prv, 1), vptr(v_cur, 0), true,
+                  msk_cur, 2 * idx + 1, 0, tb, k_lds + (unsigned)(k_ld * TILE * 2) + wave_lds);
+        half_step(s1, s0, pa, pb, kptr(k_nxt, 0), kptr(k_nxt, 1), vptr(v_cur, 0), vptr(v_cur, 1), true,
+                  msk_nxt, 2 * idx + 2, 1, tb, v_lds + (unsigned)(v_ld * TILE * 2) + wave_lds);
         dma_wait_older();
     }
     dma_wait_all();     // nothing may still be landing in LDS when the wavefront ends
     // P V of the very last block (its first operands are already in flight)
     {
-        const __bf16* vst = v_block_ptr(n_iter - 1, 1);
+        const __bf16* vst = vptr(v_cur, 1);
 #pragma unroll
         for (int i = 0; i < NOP; ++i) {
             if (i + AHEAD < NOP) vq[i + AHEAD] = v_operand(vst, i + AHEAD);
