@@ -113,6 +113,7 @@ def main():
 
     bm, bn = B.difa_tile_shape(wl.D)
     _, items, _ = B.difa_worklist_build(wl.B, wl.H, wl.head_plan, wl.window, wl.n_text, wl.n_img, bm, bn)
+    items = items[items["q_tile"] >= 0] if items is not None else items
     executed = float(items["n_tiles"].sum()) * bm * bn * 4 * wl.D if items is not None and len(items) else 0.0
 
     computed_tflops = fl["computed"] / (wall_ms * 1e-3) * 1e-12 if fl["computed"] else 0.0

@@ -127,15 +127,19 @@ int32_t difa_tile_shape(int32_t head_dim, int32_t dtype, int32_t* bm, int32_t* b
 
 /*
  * Compile a head plan into work items (HOST only, no GPU needed).
+ *   n_xcd           1: records ordered most-key-tiles-first.  > 1: the list is laid out for a GPU
+ *                   whose workgroup p runs on accelerator die p % n_xcd (each with its own L2):
+ *                   n_xcd interleaved queues of equal total cost, heads kept together on a die,
+ *                   short queues padded with records whose q_tile is -1.
  *   items/capacity  HOST array to fill (may be NULL with capacity 0 to only count).
- *   n_items_out     number of records the plan needs (written also when capacity is short).
+ *   n_items_out     number of records, padding included (written also when capacity is short).
  *   copy_heads/n_copy_out  optional: int32[heads] receiving the indices of CACHE heads.
- * Records are ordered most-key-tiles-first.  Returns DIFA_OK, INVALID_ARG (bad mode/window/
- * sizes) or ALLOC (capacity too small; nothing useful in items).
+ * Returns DIFA_OK, INVALID_ARG (bad mode/window/sizes) or ALLOC (capacity too small; nothing
+ * useful in items).
  */
 difa_status_t difa_worklist_build(int32_t batch, int32_t heads, const int32_t* head_plan,
                                   const int32_t* window, int32_t n_text, int32_t n_img,
-                                  int32_t bm, int32_t bn, difa_work_item_t* items,
+                                  int32_t bm, int32_t bn, int32_t n_xcd, difa_work_item_t* items,
                                   int32_t capacity, int32_t* n_items_out, int32_t* copy_heads,
                                   int32_t* n_copy_out);
 

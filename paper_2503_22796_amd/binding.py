@@ -48,7 +48,7 @@ def _load():
     L.difa_tile_shape.restype = i32
     L.difa_tile_shape.argtypes = [i32, i32, i32p, i32p]
     L.difa_worklist_build.restype = ctypes.c_int
-    L.difa_worklist_build.argtypes = [i32, i32, vp, vp, i32, i32, i32, i32, vp, i32, i32p, vp, i32p]
+    L.difa_worklist_build.argtypes = [i32, i32, vp, vp, i32, i32, i32, i32, i32, vp, i32, i32p, vp, i32p]
     L.difa_plan_timing_enable.restype = ctypes.c_int
     L.difa_plan_timing_enable.argtypes = [vp, i32]
     L.difa_plan_timing_read.restype = ctypes.c_int
@@ -85,19 +85,19 @@ def _i32(a):
     return None if a is None else np.ascontiguousarray(np.asarray(a, dtype=np.int32))
 
 
-def difa_worklist_build(batch, heads, head_plan, window, n_text, n_img, bm, bn):
+def difa_worklist_build(batch, heads, head_plan, window, n_text, n_img, bm, bn, n_xcd=1):
     """Returns (status, items as a numpy structured array, CACHE-head indices)."""
     hp, win = _i32(head_plan), _i32(window)
     n_items, n_copy = ctypes.c_int32(0), ctypes.c_int32(0)
     copy_heads = np.zeros(max(int(heads), 1), dtype=np.int32)
     st = lib.difa_worklist_build(batch, heads, hp.ctypes.data if hp is not None else None,
-                                 win.ctypes.data if win is not None else None, n_text, n_img, bm, bn,
+                                 win.ctypes.data if win is not None else None, n_text, n_img, bm, bn, n_xcd,
                                  None, 0, ctypes.byref(n_items), None, ctypes.byref(n_copy))
     if st != DIFA_OK:
         return st, None, None
     items = (difa_work_item_t * max(n_items.value, 1))()
     st = lib.difa_worklist_build(batch, heads, hp.ctypes.data, win.ctypes.data if win is not None else None,
-                                 n_text, n_img, bm, bn, ctypes.cast(items, ctypes.c_void_p), n_items.value,
+                                 n_text, n_img, bm, bn, n_xcd, ctypes.cast(items, ctypes.c_void_p), n_items.value,
                                  ctypes.byref(n_items), copy_heads.ctypes.data, ctypes.byref(n_copy))
     arr = np.frombuffer(items, dtype=np.dtype([(n, np.int32) for n, _ in difa_work_item_t._fields_]),
                         count=n_items.value).copy()

@@ -14,10 +14,11 @@
 namespace {
 
 constexpr int kSlots = 8;  // distinct (head plan, n_text, n_img) work lists kept resident
+constexpr int kXcd = 8;    // accelerator dies of an MI355X: workgroup p runs on die p % 8
 
 struct Slot {
     std::vector<int32_t> key;
-    void* h_buf = nullptr;  // pinned host staging: items, then CACHE-head indices
+    void* h_buf = nullptr;  // pinned host staging: CACHE-head indices, then the work records
     void* d_buf = nullptr;  // device copy
     int32_t n_items = 0, n_copy = 0;
     hipEvent_t uploaded = nullptr;  // recorded after the host-to-device copy
@@ -39,7 +40,7 @@ struct difa_plan {
     float scale;
     int32_t bm, bn;
     int32_t item_capacity;
-    size_t buf_bytes, copy_off;
+    size_t buf_bytes, items_off;   // records start items_off bytes into a slot buffer
     Slot slots[kSlots];
     uint64_t clock = 0;
     std::string err;
@@ -171,14 +172,14 @@ extern "C" difa_status_t difa_plan_create(const difa_plan_desc_t* desc, difa_pla
     p->scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)desc->head_dim);
     difa_tile_shape(desc->head_dim, desc->dtype, &p->bm, &p->bn);
     const int64_t q_tiles = ((int64_t)desc->max_tokens + p->bm - 1) / p->bm;
-    const int64_t cap = (int64_t)desc->batch * desc->heads * q_tiles;
+    const int64_t cap = (int64_t)desc->batch * desc->heads * q_tiles * kXcd;   // padded queues: at most kXcd x the records
     if (cap > (int64_t)1 << 26) {
         delete p;
         return fail(nullptr, DIFA_ERR_UNSUPPORTED, "batch*heads*query tiles exceeds the work-list limit");
     }
     p->item_capacity = (int32_t)cap;
-    p->copy_off = (size_t)cap * sizeof(difa_work_item_t);
-    p->buf_bytes = p->copy_off + (size_t)desc->heads * sizeof(int32_t);
+    p->items_off = ((size_t)desc->heads * sizeof(int32_t) + 63) / 64 * 64;
+    p->buf_bytes = p->items_off + (size_t)cap * sizeof(difa_work_item_t);
 
     DeviceGuard guard;
     e = guard.enter(desc->device);
@@ -289,11 +290,12 @@ extern "C" difa_status_t difa_joint_attention(difa_plan_t* p, const void* q, con
         }
         lru->valid = false;
         int32_t n_items = 0, n_copy = 0;
-        difa_status_t st = difa_worklist_build(B, H, head_plan, window, n_text, n_img, p->bm, p->bn,
-                                               (difa_work_item_t*)lru->h_buf, p->item_capacity, &n_items,
-                                               (int32_t*)((char*)lru->h_buf + p->copy_off), &n_copy);
+        difa_status_t st = difa_worklist_build(B, H, head_plan, window, n_text, n_img, p->bm, p->bn, kXcd,
+                                               (difa_work_item_t*)((char*)lru->h_buf + p->items_off),
+                                               p->item_capacity, &n_items, (int32_t*)lru->h_buf, &n_copy);
         if (st != DIFA_OK) return fail(p, st, "work-list compilation failed");
-        e = hipMemcpyAsync(lru->d_buf, lru->h_buf, p->buf_bytes, hipMemcpyHostToDevice, stream);
+        e = hipMemcpyAsync(lru->d_buf, lru->h_buf, p->items_off + (size_t)n_items * sizeof(difa_work_item_t),
+                           hipMemcpyHostToDevice, stream);   // only the part in use
         if (e == hipSuccess) e = hipEventRecord(lru->uploaded, stream);
         if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("uploading the work list", e));
         lru->key = key;
@@ -323,7 +325,7 @@ extern "C" difa_status_t difa_joint_attention(difa_plan_t* p, const void* q, con
         difa::CopyArgs c{};
         c.src = cache;
         c.dst = out;
-        c.copy_heads = (const int32_t*)((const char*)slot->d_buf + p->copy_off);
+        c.copy_heads = (const int32_t*)slot->d_buf;
         c.stride_b = sb * (int64_t)es; c.stride_h = sh * (int64_t)es; c.stride_n = sn * (int64_t)es;
         c.batch = B; c.n_copy = slot->n_copy; c.n_tokens = N;
         c.vec_per_row = (int32_t)(D * es / 16);
@@ -339,7 +341,7 @@ extern "C" difa_status_t difa_joint_attention(difa_plan_t* p, const void* q, con
     if (slot->n_items > 0) {
         difa::AttnArgs a{};
         a.q = q; a.k = k; a.v = v; a.out = out;
-        a.items = (const difa_work_item_t*)slot->d_buf;
+        a.items = (const difa_work_item_t*)((const char*)slot->d_buf + p->items_off);
         a.stride_b = sb; a.stride_h = sh; a.stride_n = sn;
         a.heads = H; a.n_tokens = N; a.n_text = n_text;
         a.scale = p->scale;

@@ -6,6 +6,8 @@
 // to visit (text tiles, then the tiles its rows' bands touch) and which of them are free of
 // any masked pair, so the kernel never loads a fully masked tile and applies the element
 // mask (Sec. 3.1: text quadrants whole, image-image band |i-j| <= w) only on edge tiles.
+#include <stdint.h>
+
 #include <algorithm>
 #include <vector>
 
@@ -64,11 +66,11 @@ extern "C" int32_t difa_tile_shape(int32_t head_dim, int32_t dtype, int32_t* bm,
 
 extern "C" difa_status_t difa_worklist_build(int32_t batch, int32_t heads, const int32_t* head_plan,
                                              const int32_t* window, int32_t n_text, int32_t n_img,
-                                             int32_t bm, int32_t bn, difa_work_item_t* items,
+                                             int32_t bm, int32_t bn, int32_t n_xcd, difa_work_item_t* items,
                                              int32_t capacity, int32_t* n_items_out,
                                              int32_t* copy_heads, int32_t* n_copy_out) {
     if (!head_plan || !n_items_out || batch < 1 || heads < 1 || n_text < 0 || n_img < 0 ||
-        bm < 1 || bn < 1 || capacity < 0 || (capacity > 0 && !items))
+        bm < 1 || bn < 1 || n_xcd < 1 || n_xcd > 64 || capacity < 0 || (capacity > 0 && !items))
         return DIFA_ERR_INVALID_ARG;
     const int64_t n64 = (int64_t)n_text + (int64_t)n_img;
     if (n64 < 1 || n64 > (int64_t)1 << 30) return DIFA_ERR_INVALID_ARG;
@@ -83,54 +85,103 @@ extern "C" difa_status_t difa_worklist_build(int32_t batch, int32_t heads, const
     const int n_kv_tiles = (g.n_tokens + bn - 1) / bn;
     const int text_tiles = (n_text + bn - 1) / bn;  // tiles that hold at least one text key
 
+    // Records are first collected head by head (query tiles in ascending order).
+    struct HeadSpan { size_t first, count; int64_t cost; };
     std::vector<difa_work_item_t> recs;
+    std::vector<HeadSpan> spans;
     int n_copy = 0;
-    for (int h = 0; h < heads; ++h) {
-        const int mode = head_plan[h];
-        if (mode == DIFA_HEAD_CACHE) {
-            if (copy_heads) copy_heads[n_copy] = h;
-            ++n_copy;
-            continue;
-        }
-        // A band that covers the whole image is full attention.
-        const bool full = (mode == DIFA_HEAD_FULL) || (window[h] >= n_img - 1);
-        const int w = full ? -1 : window[h];
-        for (int qt = 0; qt < n_q_tiles; ++qt) {
-            const int i0 = qt * bm, i1 = std::min(i0 + bm, g.n_tokens);
-            difa_work_item_t r{};
-            r.q_tile = qt;
-            r.window = w;
-            if (full) {
-                r.kv0_end = n_kv_tiles;
-                r.kv1_begin = r.kv1_end = n_kv_tiles;
-            } else {
-                r.kv0_end = text_tiles;
-                if (i0 < n_text) {  // the tile holds text queries: they see every key
-                    r.kv1_begin = text_tiles;
-                    r.kv1_end = n_kv_tiles;
-                } else {
-                    const int lo = std::max(n_text, i0 - w);
-                    const int hi = std::min(g.n_tokens - 1, (i1 - 1) + w);
-                    r.kv1_begin = std::max(text_tiles, lo / bn);
-                    r.kv1_end = std::max(r.kv1_begin, hi / bn + 1);
+    for (int b = 0; b < batch; ++b) {
+        for (int h = 0; h < heads; ++h) {
+            const int mode = head_plan[h];
+            if (mode == DIFA_HEAD_CACHE) {
+                if (b == 0) {
+                    if (copy_heads) copy_heads[n_copy] = h;
+                    ++n_copy;
                 }
+                continue;
             }
-            int b0, e0;
-            mask_free_run(g, w, i0, i1, 0, r.kv0_end, true, &b0, &e0);
-            r.nm0_end = e0;
-            mask_free_run(g, w, i0, i1, r.kv1_begin, r.kv1_end, false, &r.nm1_begin, &r.nm1_end);
-            r.n_tiles = r.kv0_end + (r.kv1_end - r.kv1_begin);
-            for (int b = 0; b < batch; ++b) {
+            // A band that covers the whole image is full attention.
+            const bool full = (mode == DIFA_HEAD_FULL) || (window[h] >= n_img - 1);
+            const int w = full ? -1 : window[h];
+            HeadSpan span{recs.size(), 0, 0};
+            for (int qt = 0; qt < n_q_tiles; ++qt) {
+                const int i0 = qt * bm, i1 = std::min(i0 + bm, g.n_tokens);
+                difa_work_item_t r{};
                 r.bh = b * heads + h;
+                r.q_tile = qt;
+                r.window = w;
+                if (full) {
+                    r.kv0_end = n_kv_tiles;
+                    r.kv1_begin = r.kv1_end = n_kv_tiles;
+                } else {
+                    r.kv0_end = text_tiles;
+                    if (i0 < n_text) {  // the tile holds text queries: they see every key
+                        r.kv1_begin = text_tiles;
+                        r.kv1_end = n_kv_tiles;
+                    } else {
+                        const int lo = std::max(n_text, i0 - w);
+                        const int hi = std::min(g.n_tokens - 1, (i1 - 1) + w);
+                        r.kv1_begin = std::max(text_tiles, lo / bn);
+                        r.kv1_end = std::max(r.kv1_begin, hi / bn + 1);
+                    }
+                }
+                int b0, e0;
+                mask_free_run(g, w, i0, i1, 0, r.kv0_end, true, &b0, &e0);
+                r.nm0_end = e0;
+                mask_free_run(g, w, i0, i1, r.kv1_begin, r.kv1_end, false, &r.nm1_begin, &r.nm1_end);
+                r.n_tiles = r.kv0_end + (r.kv1_end - r.kv1_begin);
                 recs.push_back(r);
+                span.cost += r.n_tiles;
             }
+            span.count = recs.size() - span.first;
+            spans.push_back(span);
         }
     }
-    // Heaviest records first: the hardware hands workgroups out in index order, so the long
-    // full-attention tiles start early and the short band tiles fill the tail.
-    std::stable_sort(recs.begin(), recs.end(), [](const difa_work_item_t& a, const difa_work_item_t& b) {
-        return a.n_tiles > b.n_tiles;
-    });
+    if (n_xcd == 1) {
+        // Heaviest records first: the hardware hands workgroups out in index order, so the long
+        // full-attention tiles start early and the short band tiles fill the tail.
+        std::stable_sort(recs.begin(), recs.end(), [](const difa_work_item_t& a, const difa_work_item_t& b) {
+            return a.n_tiles > b.n_tiles;
+        });
+    } else if (!recs.empty()) {
+        // Workgroup p runs on accelerator die p % n_xcd, and every die has its own L2.  If the query
+        // tiles of one head are spread over all dies, each die streams that head's K and V from
+        // memory: n_xcd times the traffic.  So the records are laid out as n_xcd queues, queue x at
+        // positions x, x + n_xcd, ...: heads in order of decreasing cost, the whole sequence cut into
+        // n_xcd runs of equal cost, so that a head lives on one die (two where a cut falls inside it),
+        // its query tiles run side by side and share the K/V tiles in that die's L2, and every die
+        // gets the same amount of work.  Short queues are padded with records whose q_tile is -1.
+        std::stable_sort(spans.begin(), spans.end(), [](const HeadSpan& a, const HeadSpan& b) { return a.cost > b.cost; });
+        int64_t total = 0;
+        for (const HeadSpan& sp : spans) total += sp.cost;
+        std::vector<std::vector<difa_work_item_t>> queue((size_t)n_xcd);
+        int64_t cum = 0;
+        for (const HeadSpan& sp : spans)
+            for (size_t k = 0; k < sp.count; ++k) {
+                const difa_work_item_t& r = recs[sp.first + k];
+                int64_t x = total > 0 ? ((2 * cum + r.n_tiles) * n_xcd) / (2 * total) : 0;
+                x = std::min<int64_t>(std::max<int64_t>(x, 0), n_xcd - 1);
+                queue[(size_t)x].push_back(r);
+                cum += r.n_tiles;
+            }
+        // Inside a queue: longest records first (a query tile that holds text rows visits every key
+        // tile and would otherwise start late and finish last), in classes of 16 key tiles so that
+        // records of one head, which differ by a tile or two, stay next to each other.
+        for (auto& q : queue)
+            std::stable_sort(q.begin(), q.end(), [](const difa_work_item_t& a, const difa_work_item_t& b) {
+                return a.n_tiles / 16 > b.n_tiles / 16;
+            });
+        size_t longest = 0;
+        for (const auto& q : queue) longest = std::max(longest, q.size());
+        difa_work_item_t pad{};
+        pad.q_tile = -1;
+        pad.window = -1;
+        std::vector<difa_work_item_t> laid(longest * (size_t)n_xcd, pad);
+        for (int x = 0; x < n_xcd; ++x)
+            for (size_t k = 0; k < queue[(size_t)x].size(); ++k) laid[k * (size_t)n_xcd + (size_t)x] = queue[(size_t)x][k];
+        while (!laid.empty() && laid.back().q_tile < 0) laid.pop_back();
+        recs.swap(laid);
+    }
     *n_items_out = (int32_t)recs.size();
     if (n_copy_out) *n_copy_out = n_copy;
     if ((int64_t)recs.size() > capacity) return capacity == 0 && !items ? DIFA_OK : DIFA_ERR_ALLOC;

@@ -42,20 +42,41 @@ CASES = [
 
 @pytest.mark.parametrize("n_text,n_img,bm,bn,heads", CASES)
 @pytest.mark.parametrize("batch", [1, 2])
-def test_records_match_brute_force(n_text, n_img, bm, bn, heads, batch):
+@pytest.mark.parametrize("n_xcd", [1, 3, 8])
+def test_records_match_brute_force(n_text, n_img, bm, bn, heads, batch, n_xcd):
     N = n_text + n_img
     hp = [m for m, _ in heads]
     win = [w for _, w in heads]
     H = len(heads)
-    st, items, copy_heads = B.difa_worklist_build(batch, H, hp, win, n_text, n_img, bm, bn)
+    st, laid, copy_heads = B.difa_worklist_build(batch, H, hp, win, n_text, n_img, bm, bn, n_xcd)
     assert st == B.DIFA_OK
     assert list(copy_heads) == [h for h in range(H) if hp[h] == CACHE]
     n_q = (N + bm - 1) // bm
     computed = [h for h in range(H) if hp[h] != CACHE]
+    items = laid[laid["q_tile"] >= 0]            # the rest is padding of short queues
     assert len(items) == batch * len(computed) * n_q
     seen = set()
-    tiles = [int(x) for x in items["n_tiles"]]
-    assert tiles == sorted(tiles, reverse=True), "records must be ordered heaviest first"
+    if n_xcd == 1:
+        assert len(laid) == len(items)
+        tiles = [int(x) for x in items["n_tiles"]]
+        assert tiles == sorted(tiles, reverse=True), "records must be ordered heaviest first"
+    else:
+        # queue x = positions x, x + n_xcd, ...: equal cost, padding only behind a queue's records
+        costs = []
+        for x in range(n_xcd):
+            q = laid[x::n_xcd]
+            real = q["q_tile"] >= 0
+            assert not (np.diff(real.astype(int)) > 0).any(), "padding inside a queue"
+            costs.append(int(q["n_tiles"][real].sum()))
+        heaviest = int(items["n_tiles"].max()) if len(items) else 0
+        assert max(costs) - min(costs) <= 2 * heaviest, f"queues out of balance: {costs}"
+        # a head is split over at most two neighbouring queues... unless it is cut more than once
+        # because it alone outweighs a queue's share
+        share = sum(costs) / n_xcd
+        for bh in set(items["bh"].tolist()):
+            where = sorted({int(i) % n_xcd for i in np.nonzero((laid["bh"] == bh) & (laid["q_tile"] >= 0))[0]})
+            head_cost = int(items["n_tiles"][items["bh"] == bh].sum())
+            assert len(where) <= 2 + int(head_cost // max(share, 1)), (bh, where)
     for r in items:
         b, h = divmod(int(r["bh"]), H)
         assert 0 <= b < batch and h in computed
@@ -83,15 +104,16 @@ def test_records_match_brute_force(n_text, n_img, bm, bn, heads, batch):
 def test_flux_2k_shape_tile_counts():
     # image-only query tile of an arrow head visits 8 text tiles + the band tiles
     bm, bn = B.difa_tile_shape(128)
-    st, items, _ = B.difa_worklist_build(1, 2, [ARROW, FULL], [512, 0], 512, 16384, bm, bn)
+    st, items, _ = B.difa_worklist_build(1, 2, [ARROW, FULL], [512, 0], 512, 16384, bm, bn, 8)
     assert st == B.DIFA_OK
+    items = items[items["q_tile"] >= 0]
     N = 16896
     assert len(items) == 2 * ((N + bm - 1) // bm)
     full = items[items["window"] == -1]
     assert (full["n_tiles"] == N // bn).all() and (full["nm0_end"] == N // bn).all()
     arrow = items[items["window"] == 512]
-    mid = arrow[arrow["q_tile"] == 60][0]
-    i0 = 60 * bm
+    mid = arrow[arrow["q_tile"] == 30][0]
+    i0 = 30 * bm
     lo, hi = i0 - 512, i0 + bm - 1 + 512
     assert mid["kv0_end"] == 8 and mid["nm0_end"] == 8
     assert mid["kv1_begin"] == lo // bn and mid["kv1_end"] == hi // bn + 1
