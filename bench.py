@@ -118,10 +118,15 @@ def main():
 
     computed_tflops = fl["computed"] / (wall_ms * 1e-3) * 1e-12 if fl["computed"] else 0.0
     achieved = fl["computed"] / (attn_avg * 1e-3) * 1e-12 if launches and fl["computed"] else 0.0
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")   # measured with rocprofv3 --pmc, see profiles/
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(wl.name, {}).get("traffic_bytes")
     if fl["computed"]:
         roofline = {"bound": "mfma", "kernel": f"attn_bf16_kernel<{wl.D}>", "achieved": achieved,
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                    "traffic": None, "avg_kernel_ms": attn_avg, "flop_per_launch": fl["computed"]}
+                    "traffic": traffic, "traffic_unit": "bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled on a known copy)",
+                    "algorithmic_bytes": by["attention"], "avg_kernel_ms": attn_avg, "flop_per_launch": fl["computed"]}
     else:
         gbs = by["cache_copy"] / (copy_avg * 1e-3) * 1e-9 if copy_avg > 0 else 0.0
         roofline = {"bound": "hbm", "kernel": "cache_copy_kernel", "achieved": gbs, "peak": 8000.0,
