@@ -65,6 +65,21 @@ __device__ __forceinline__ bf16x4 lds_read_tr16(const __bf16* p) {
     return __builtin_bit_cast(bf16x4, r);
 }
 
+// S^T = K Q^T MFMAs are written as assembly so that the register classes are fixed: the scores
+// accumulate in ordinary vector registers, where the softmax arithmetic reads them directly (the
+// compiler's own choice for a kernel this size is accumulation registers plus one copy per score),
+// and the Q operand sits in accumulation registers, which only matrix instructions read.
+// The hardware does not interlock a vector instruction that reads a matrix result too early and the
+// compiler does not see through the assembly, so every reader is either a full half-step away or
+// preceded by an explicit wait (mfma_results_visible).
+__device__ __forceinline__ void mfma_s_first(floatx16& d, const bf16x8& k, const bf16x8& q) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(k), "a"(q));
+}
+__device__ __forceinline__ void mfma_s_acc(floatx16& d, const bf16x8& k, const bf16x8& q) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(k), "a"(q));
+}
+__device__ __forceinline__ void mfma_results_visible() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
+
 struct RowState {
     float m;       // reference maximum (log2 domain) the weights are expressed against
     float l;       // running sum of this lane's half of the keys
@@ -80,7 +95,8 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     constexpr int TILE = kBN * D;           // elements of one K or V tile
     constexpr int NSK = 4;                  // LDS ring depth for K tiles: two in use, one landed, one being loaded
     constexpr int NSV = 5;                  // ... and for V tiles (P V trails S^T by one more block)
-    constexpr float kBump = 40.0f;          // the reference maximum moves only when exceeded by 2^40
+    constexpr float kTrip = 0x1p40f;        // a block row sum beyond this sends the wavefront to the renormalising side path
+    constexpr float kBump = 16.0f;          // ... where a row's reference moves if its block maximum exceeds it by 2^16
 
     // K rows: 16-byte chunk c of row r is stored at chunk c ^ (r % CPR)       (conflict-free b128 reads)
     // V rows: chunk c of row r is stored at chunk c ^ (2 * (r % 4))          (conflict-free transpose reads)
@@ -212,16 +228,15 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     auto qk_block = [&](int idx, int jb, floatx16 (&s)[2]) {
         const __bf16* kst = &Ksm[(idx % NSK) * TILE + 32 * jb * D];
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[qb][r] = 0.f;
-#pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const bf16x8 ka = *(const bf16x8*)(kst + koff[ks]);
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb)
-                s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[qb][ks], s[qb], 0, 0, 0);
+            for (int qb = 0; qb < 2; ++qb) {
+                if (ks == 0) mfma_s_first(s[qb], ka, qf[qb][ks]);
+                else mfma_s_acc(s[qb], ka, qf[qb][ks]);
+            }
         }
+        mfma_results_visible();
     };
     auto mask_block = [&](int j0, floatx16 (&s)[2]) {
 #pragma unroll
@@ -234,77 +249,86 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
                 s[qb][r] = ok ? s[qb][r] : -INFINITY;
             }
     };
-    // ---- softmax of one 32-key block, cut into 32 small VALU pieces that are laid between MFMAs
-    // (a wavefront's own VALU work hides behind its MFMAs only in the few cycles after each issue).
-    //   pieces 0..7  : copy 4 scores of the block out of the accumulators, fold them into the block maximum
-    //   pieces 8, 9  : finish the maximum across the two wavefront halves, move the reference maximum if
-    //                  needed, produce the rescale factor (one row block each)
-    //   pieces 12..27: one score pair each -> two weights as bf16 B operands, added to the row sum
+    // ---- softmax of one 32-key block, cut into 16 small VALU pieces, one per slot, laid between the
+    // MFMAs (a wavefront issues roughly one VALU instruction per 6 cycles, so only about 6 of them fit
+    // behind one MFMA: the steady state spends nothing on a running maximum).
+    //   piece s: scores 2*(s&7), 2*(s&7)+1 of row block s>>3 -> two weights 2^(score*c - reference) as
+    //   bf16 B operands, added to the block's row sum
+    // The reference of a row is NOT the running maximum: it is set from the first block that holds an
+    // allowed key and afterwards moves only when a weight outgrows 2^kTrip.  That is detected after
+    // the fact, from the block's row sum, and repaired on a rare side path (renormalise() below), so
+    // the hot path needs no maximum at all.  Weights are at most 2^kTrip * 16: bf16 has fp32's exponent
+    // range, the row sum and O stay below 2^kTrip * N * max|v| < 2^70, far inside fp32, and the
+    // common factor cancels in O / l.
     // Each piece ends in an empty volatile asm on its results: that keeps it in its slot (otherwise the
-    // optimizer sinks the arithmetic to the block that uses it).  The online-softmax state advances
-    // once per block.
+    // optimizer sinks the arithmetic to the block that uses it).
     auto pin = [](float& x) { asm volatile("" : "+v"(x)); };
-    auto softmax_piece = [&](int h, const floatx16 (&sc)[2], float (&sv)[2][16], float (&tmax)[2],
-                             float (&mneg)[2], float (&alpha)[2], bf16x8 (&pw)[2][2]) __attribute__((always_inline)) {
-        if (h < 8) {
-            const int qb = h >> 2, r0 = (h & 3) * 4;
+    auto softmax_piece = [&](int s, const floatx16 (&sc)[2], const float (&mneg)[2], float (&lb)[2],
+                             bf16x8 (&pw)[2][2]) __attribute__((always_inline)) {
+        const int qb = s >> 3, r = 2 * (s & 7);
+        bf16x2 ones;
+        ones[0] = (__bf16)1.0f;
+        ones[1] = (__bf16)1.0f;
+        floatx2 pf;
+        pf[0] = __builtin_amdgcn_exp2f(fmaf(sc[qb][r], c, mneg[qb]));
+        pf[1] = __builtin_amdgcn_exp2f(fmaf(sc[qb][r + 1], c, mneg[qb]));
+        bf16x2 pr = __builtin_convertvector(pf, bf16x2);             // the weights that enter P V ...
+        unsigned bits = __builtin_bit_cast(unsigned, pr);
+        asm volatile("" : "+v"(bits));
+        pr = __builtin_bit_cast(bf16x2, bits);
+        pw[qb][r >> 3][r & 7] = pr[0];
+        pw[qb][r >> 3][(r & 7) + 1] = pr[1];
+        lb[qb] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, lb[qb], false);   // ... are the ones summed
+        pin(lb[qb]);
+    };
+    // Rare side path, uniform over the wavefront: some row of block g produced a weight beyond 2^kTrip
+    // (always the case for the first block, whose rows still carry the initial reference).  Every row
+    // whose block maximum exceeds its reference by more than 2^kBump takes that maximum as its new
+    // reference; the block's weights and row sums are recomputed, the running sums and O are scaled.
+    // The accumulators live in accumulation registers and are scaled in place there; the waits cover
+    // MFMA results still in flight.
+    auto renormalise = [&](const floatx16 (&sc)[2], float (&mneg)[2], float (&lb)[2], bf16x8 (&pw)[2][2]) __attribute__((always_inline)) {
+        float alpha[2];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) sv[qb][r0 + r] = sc[qb][r0 + r];
-            tmax[qb] = fmaxf(fmaxf(tmax[qb], sv[qb][r0]), sv[qb][r0 + 1]);
-            tmax[qb] = fmaxf(fmaxf(tmax[qb], sv[qb][r0 + 2]), sv[qb][r0 + 3]);
-            pin(tmax[qb]);
-        } else if (h < 10) {
-            const int qb = h - 8;
-            const float t = halves_max(tmax[qb]) * c;
-            // The reference maximum only moves when it is exceeded by more than 2^kBump.  Weights are
-            // 2^(score - reference) <= 2^kBump: bf16 has fp32's exponent range, the row sum and O stay
-            // below 2^kBump * N * max|v| < 2^60, far inside fp32, and the common factor cancels in O / l.
-            // So after the first block has set the reference, O is practically never rescaled.
+        for (int qb = 0; qb < 2; ++qb) {
+            float tmax = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sc[qb][r]);
+            const float t = halves_max(tmax) * c;
             const float m_old = rs[qb].m;
             const float m_new = t > m_old + kBump ? t : m_old;
             alpha[qb] = __builtin_amdgcn_exp2f(m_old - m_new);
             rs[qb].m = m_new;
             rs[qb].l *= alpha[qb];
             mneg[qb] = -m_new;
-            pin(mneg[qb]);
-            pin(alpha[qb]);
-        } else if (h >= 12 && h < 28) {
-            const int pi = h - 12, qb = pi >> 3, r = 2 * (pi & 7);
-            bf16x2 ones;
-            ones[0] = (__bf16)1.0f;
-            ones[1] = (__bf16)1.0f;
-            floatx2 pf;
-            pf[0] = __builtin_amdgcn_exp2f(fmaf(sv[qb][r], c, mneg[qb]));
-            pf[1] = __builtin_amdgcn_exp2f(fmaf(sv[qb][r + 1], c, mneg[qb]));
-            bf16x2 pr = __builtin_convertvector(pf, bf16x2);             // the weights that enter P V ...
-            unsigned bits = __builtin_bit_cast(unsigned, pr);
-            asm volatile("" : "+v"(bits));
-            pr = __builtin_bit_cast(bf16x2, bits);
-            pw[qb][r >> 3][r & 7] = pr[0];
-            pw[qb][r >> 3][(r & 7) + 1] = pr[1];
-            rs[qb].l = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs[qb].l, false);   // ... are the ones summed
-            pin(rs[qb].l);
+            lb[qb] = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; r += 2) {
+                bf16x2 ones;
+                ones[0] = (__bf16)1.0f;
+                ones[1] = (__bf16)1.0f;
+                floatx2 pf;
+                pf[0] = __builtin_amdgcn_exp2f(fmaf(sc[qb][r], c, mneg[qb]));
+                pf[1] = __builtin_amdgcn_exp2f(fmaf(sc[qb][r + 1], c, mneg[qb]));
+                const bf16x2 pr = __builtin_convertvector(pf, bf16x2);
+                pw[qb][r >> 3][r & 7] = pr[0];
+                pw[qb][r >> 3][(r & 7) + 1] = pr[1];
+                lb[qb] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, lb[qb], false);
+            }
         }
-    };
-    auto rescale = [&](const float (&alpha)[2]) {
-        // Uniform over the wavefront and rare: taken only when some row moved its reference maximum.
-        // The accumulators live in accumulation registers; they are scaled in place there so that the
-        // hot path never has to move them.  The waits cover MFMA results still in flight.
-        if (__builtin_expect(__builtin_amdgcn_ballot_w64(alpha[0] != 1.0f || alpha[1] != 1.0f) != 0, 0)) {
-            asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-                for (int qb = 0; qb < 2; ++qb)
+            for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        float e = o[db][qb][r], t;
-                        asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\tv_accvgpr_write_b32 %0, %1"
-                                     : "+a"(e), "=&v"(t) : "v"(alpha[qb]));
-                        o[db][qb][r] = e;
-                    }
-            asm volatile("s_nop 7" ::: "memory");
-        }
+                for (int r = 0; r < 16; ++r) {
+                    float e = o[db][qb][r], t;
+                    asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\tv_accvgpr_write_b32 %0, %1"
+                                 : "+a"(e), "=&v"(t) : "v"(alpha[qb]));
+                    o[db][qb][r] = e;
+                }
+        asm volatile("s_nop 7" ::: "memory");
     };
     // ---- O^T += V^T P^T: k-slot e of a lane is key 32*jb + 16*tt + 4*half + (e<4 ? e : e+4)
     // ---- operand fetches from LDS
@@ -345,11 +369,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
                          bf16x8 (&p_cur)[2][2], const __bf16* kst_nxt, const __bf16* kst_after,
                          const __bf16* vst_prev, const __bf16* vst_cur, bool with_pv, bool mask_nxt,
                          int blk_nxt, int dma_tensor, unsigned dma_tb, unsigned dma_dst) __attribute__((always_inline)) {
-        float sv[2][16], tmax[2] = {-INFINITY, -INFINITY}, mneg[2], alpha[2];
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s_nxt[qb][r] = 0.f;
+        float mneg[2] = {-rs[0].m, -rs[1].m}, lb[2] = {0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < 16; ++s) {
             const int j = s >> 1, qb = s & 1;
@@ -364,20 +384,26 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
                         vq[jn - NOP] = v_operand(vst_cur, jn - NOP);
                     }
                 }
-                s_nxt[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kq[j], qf[qb][j], s_nxt[qb], 0, 0, 0);
+                if (j == 0) mfma_s_first(s_nxt[qb], kq[j], qf[qb][j]);
+                else mfma_s_acc(s_nxt[qb], kq[j], qf[qb][j]);
             }
-            softmax_piece(2 * s, s_cur, sv, tmax, mneg, alpha, p_cur);
+            softmax_piece(s, s_cur, mneg, lb, p_cur);
             if (with_pv && s < NMF)
                 o[j >> 1][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vq[j], p_prev[qb][j & 1], o[j >> 1][qb], 0, 0, 0);
-            softmax_piece(2 * s + 1, s_cur, sv, tmax, mneg, alpha, p_cur);
             // the loads of the tile three positions ahead are spread over the slots (a burst of them
             // right after the barrier stalls all four wavefronts on the one memory pipe)
             if ((s & 3) == 1 && (s >> 2) < NDMA) dma_part(dma_tensor, s >> 2, dma_tb, dma_dst);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (with_pv) rescale(alpha);
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(fmaxf(lb[0], lb[1]) > kTrip) != 0, 0))
+            renormalise(s_cur, mneg, lb, p_cur);
+        rs[0].l += lb[0];
+        rs[1].l += lb[1];
         // block number blk_nxt = 2*position + jb; its first key is only needed on this rare path
-        if (__builtin_expect(mask_nxt, 0)) mask_block(tile_of(blk_nxt >> 1) * kBN + 32 * (blk_nxt & 1), s_nxt);
+        if (__builtin_expect(mask_nxt, 0)) {
+            mfma_results_visible();
+            mask_block(tile_of(blk_nxt >> 1) * kBN + 32 * (blk_nxt & 1), s_nxt);
+        }
     };
 
     qk_block(0, 0, s0);
