@@ -93,15 +93,14 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     constexpr int DB = D / 32;              // 32-row blocks of O^T
     constexpr int CPR = D / 8;              // 16-byte chunks per K/V row
     constexpr int TILE = kBN * D;           // elements of one K or V tile
-    constexpr int NSK = 4;                  // LDS ring depth for K tiles: two in use, one landed, one being loaded
-    constexpr int NSV = 5;                  // ... and for V tiles (P V trails S^T by one more block)
+    constexpr int NS = 4;                   // LDS ring depth, K and V alike: tile p lives in stage p % 4
     constexpr float kTrip = 0x1p40f;        // a block row sum beyond this sends the wavefront to the renormalising side path
     constexpr float kBump = 16.0f;          // ... where a row's reference moves if its block maximum exceeds it by 2^16
 
     // K rows: 16-byte chunk c of row r is stored at chunk c ^ (r % CPR)       (conflict-free b128 reads)
     // V rows: chunk c of row r is stored at chunk c ^ (2 * (r % 4))          (conflict-free transpose reads)
-    __shared__ __attribute__((aligned(16))) __bf16 Ksm[NSK * TILE];
-    __shared__ __attribute__((aligned(16))) __bf16 Vsm[NSV * TILE];
+    __shared__ __attribute__((aligned(16))) __bf16 Ksm[NS * TILE];
+    __shared__ __attribute__((aligned(16))) __bf16 Vsm[NS * TILE];
 
     const difa_work_item_t it = a.items[blockIdx.x];
     if (it.q_tile < 0) return;
@@ -213,12 +212,15 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     auto tile_offset = [&](int idx) {                       // byte offset of the tile at position idx
         return idx < n_iter ? (unsigned)tile_of(idx) * tile_bytes : 0x80000000u;
     };
-    auto dma_tile = [&](int idx) {
+    auto dma_tile = [&](int idx, bool with_v) {
         const unsigned tb = tile_offset(idx);
-        const unsigned kd = k_lds + (unsigned)((idx % NSK) * TILE * 2) + wave_lds;
-        const unsigned vd = v_lds + (unsigned)((idx % NSV) * TILE * 2) + wave_lds;
+        const unsigned kd = k_lds + (unsigned)((idx % NS) * TILE * 2) + wave_lds;
+        const unsigned vd = v_lds + (unsigned)((idx % NS) * TILE * 2) + wave_lds;
 #pragma unroll
-        for (int u = 0; u < NDMA; ++u) { dma_part(0, u, tb, kd); dma_part(1, u, tb, vd); }
+        for (int u = 0; u < NDMA; ++u) {
+            dma_part(0, u, tb, kd);
+            if (with_v) dma_part(1, u, tb, vd);
+        }
     };
     // all loads done / all but the 2*NDMA youngest (= the tile issued during the current iteration) done
     auto dma_wait_all = [] { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
@@ -226,7 +228,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
 
     // ---- S^T = K Q^T for one 32-key block jb of a tile: s[qb], register r = key 32*jb + 8*(r/4) + 4*half + r%4
     auto qk_block = [&](int idx, int jb, floatx16 (&s)[2]) {
-        const __bf16* kst = &Ksm[(idx % NSK) * TILE + 32 * jb * D];
+        const __bf16* kst = &Ksm[(idx % NS) * TILE + 32 * jb * D];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const bf16x8 ka = *(const bf16x8*)(kst + koff[ks]);
@@ -249,9 +251,10 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
                 s[qb][r] = ok ? s[qb][r] : -INFINITY;
             }
     };
-    // ---- softmax of one 32-key block, cut into 16 small VALU pieces, one per slot, laid between the
-    // MFMAs (a wavefront issues roughly one VALU instruction per 6 cycles, so only about 6 of them fit
-    // behind one MFMA: the steady state spends nothing on a running maximum).
+    // ---- softmax of one 32-key block, cut into 16 pieces of six VALU instructions, one per slot, each
+    // split in two halves that sit behind the slot's two MFMAs (one wavefront per SIMD issues in order:
+    // whatever is not behind an MFMA delays the next one; the steady state spends nothing on a running
+    // maximum).
     //   piece s: scores 2*(s&7), 2*(s&7)+1 of row block s>>3 -> two weights 2^(score*c - reference) as
     //   bf16 B operands, added to the block's row sum
     // The reference of a row is NOT the running maximum: it is set from the first block that holds an
@@ -263,15 +266,21 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     // Each piece ends in an empty volatile asm on its results: that keeps it in its slot (otherwise the
     // optimizer sinks the arithmetic to the block that uses it).
     auto pin = [](float& x) { asm volatile("" : "+v"(x)); };
-    auto softmax_piece = [&](int s, const floatx16 (&sc)[2], const float (&mneg)[2], float (&lb)[2],
-                             bf16x8 (&pw)[2][2]) __attribute__((always_inline)) {
+    auto softmax_a = [&](int s, const floatx16 (&sc)[2], const float (&mneg)[2], float (&x)[2]) __attribute__((always_inline)) {
+        const int qb = s >> 3, r = 2 * (s & 7);
+        x[0] = __builtin_amdgcn_exp2f(fmaf(sc[qb][r], c, mneg[qb]));
+        x[1] = fmaf(sc[qb][r + 1], c, mneg[qb]);
+        pin(x[0]);
+        pin(x[1]);
+    };
+    auto softmax_b = [&](int s, float (&x)[2], float (&lb)[2], bf16x8 (&pw)[2][2]) __attribute__((always_inline)) {
         const int qb = s >> 3, r = 2 * (s & 7);
         bf16x2 ones;
         ones[0] = (__bf16)1.0f;
         ones[1] = (__bf16)1.0f;
         floatx2 pf;
-        pf[0] = __builtin_amdgcn_exp2f(fmaf(sc[qb][r], c, mneg[qb]));
-        pf[1] = __builtin_amdgcn_exp2f(fmaf(sc[qb][r + 1], c, mneg[qb]));
+        pf[0] = x[0];
+        pf[1] = __builtin_amdgcn_exp2f(x[1]);
         bf16x2 pr = __builtin_convertvector(pf, bf16x2);             // the weights that enter P V ...
         unsigned bits = __builtin_bit_cast(unsigned, pr);
         asm volatile("" : "+v"(bits));
@@ -341,9 +350,9 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     };
 
     // ---- prologue: tiles 0 and 1 into the ring, S^T of block (tile 0, jb 0)
-    dma_tile(0);
-    dma_tile(1);
-    dma_tile(2);
+    dma_tile(0, true);
+    dma_tile(1, true);
+    dma_tile(2, false);
     dma_wait_all();
     __syncthreads();
 
@@ -372,26 +381,29 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
         float mneg[2] = {-rs[0].m, -rs[1].m}, lb[2] = {0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < 16; ++s) {
-            const int j = s >> 1, qb = s & 1;
+            const int j = s >> 1, qb = s & 1, jn = j + AHEAD;    // operand jn is fetched while operand j is used
+            float x[2];
             if (s < NMF) {
-                if (qb == 0) {      // fetch operand j+AHEAD: of this half-step, or of the next one
-                    const int jn = j + AHEAD;
-                    if (jn < NOP) {
-                        kq[jn] = k_operand(kst_nxt, jn);
-                        if (with_pv) vq[jn] = v_operand(vst_prev, jn);
-                    } else {
-                        kq[jn - NOP] = k_operand(kst_after, jn - NOP);
-                        vq[jn - NOP] = v_operand(vst_cur, jn - NOP);
-                    }
-                }
                 if (j == 0) mfma_s_first(s_nxt[qb], kq[j], qf[qb][j]);
                 else mfma_s_acc(s_nxt[qb], kq[j], qf[qb][j]);
+                if (qb == 0) {
+                    if (jn < NOP) kq[jn] = k_operand(kst_nxt, jn);
+                    else kq[jn - NOP] = k_operand(kst_after, jn - NOP);
+                }
             }
-            softmax_piece(s, s_cur, mneg, lb, p_cur);
-            if (with_pv && s < NMF)
-                o[j >> 1][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vq[j], p_prev[qb][j & 1], o[j >> 1][qb], 0, 0, 0);
-            // the loads of the tile three positions ahead are spread over the slots (a burst of them
-            // right after the barrier stalls all four wavefronts on the one memory pipe)
+            softmax_a(s, s_cur, mneg, x);
+            __builtin_amdgcn_sched_barrier(0);
+            if (s < NMF) {
+                if (with_pv)
+                    o[j >> 1][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vq[j], p_prev[qb][j & 1], o[j >> 1][qb], 0, 0, 0);
+                if (qb == 0) {
+                    if (jn < NOP) { if (with_pv) vq[jn] = v_operand(vst_prev, jn); }
+                    else vq[jn - NOP] = v_operand(vst_cur, jn - NOP);
+                }
+            }
+            softmax_b(s, x, lb, p_cur);
+            // the loads of a later tile are spread over the slots (a burst of them right after the
+            // barrier stalls all four wavefronts on the one memory pipe)
             if ((s & 3) == 1 && (s >> 2) < NDMA) dma_part(dma_tensor, s >> 2, dma_tb, dma_dst);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -419,35 +431,36 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     auto bump = [](int& st, int n) { st = st + 1 == n ? 0 : st + 1; };
     auto kptr = [&](int st, int jb) { return &Ksm[st * TILE + 32 * jb * D]; };
     auto vptr = [&](int st, int jb) { return &Vsm[st * TILE + 32 * jb * D]; };
-    int k_cur = 0, k_nxt = 1, k_ld = 3 % NSK;               // K stages of positions idx, idx+1, idx+3
-    int v_prv = 0, v_cur = 0, v_ld = 3 % NSV;               // V stages of positions idx-1, idx, idx+3
+    int k_cur = 0, k_nxt = 1, k_ld = 3;                     // K stages of positions idx, idx+1, idx+3
+    int v_prv = 0, v_cur = 0, v_ld = 2;                     // V stages of positions idx-1, idx, idx+2
     bool msk_cur = pos_masked(0), msk_nxt = pos_masked(1);
+    unsigned tb_k = tile_offset(3), tb_v = tile_offset(2);  // tiles whose K / V loads the coming iteration issues
 
     // first tile: its even block has no predecessor whose P V would be due
 #pragma unroll
     for (int j = 0; j < AHEAD; ++j) kq[j] = k_operand(kptr(k_cur, 1), j);
-    {
-        const unsigned tb = tile_offset(3);
-        half_step(s0, s1, pb, pa, kptr(k_cur, 1), kptr(k_nxt, 0), vptr(v_cur, 0), vptr(v_cur, 0), false,
-                  msk_cur, 1, 0, tb, k_lds + (unsigned)(k_ld * TILE * 2) + wave_lds);
-        half_step(s1, s0, pa, pb, kptr(k_nxt, 0), kptr(k_nxt, 1), vptr(v_cur, 0), vptr(v_cur, 1), true,
-                  msk_nxt, 2, 1, tb, v_lds + (unsigned)(v_ld * TILE * 2) + wave_lds);
-    }
+    half_step(s0, s1, pb, pa, kptr(k_cur, 1), kptr(k_nxt, 0), vptr(v_cur, 0), vptr(v_cur, 0), false,
+              msk_cur, 1, 0, tb_k, k_lds + (unsigned)(k_ld * TILE * 2) + wave_lds);
+    half_step(s1, s0, pa, pb, kptr(k_nxt, 0), kptr(k_nxt, 1), vptr(v_cur, 0), vptr(v_cur, 1), true,
+              msk_nxt, 2, 1, tb_v, v_lds + (unsigned)(v_ld * TILE * 2) + wave_lds);
     dma_wait_older();
 
-    // Iteration idx works on tiles idx-1 (P V), idx and idx+1 (S^T), issues the loads of tile idx+3 and,
-    // before the next barrier, waits for the loads of tile idx+2 (issued one iteration earlier).
+    // Iteration idx works on tiles idx-1 (P V), idx and idx+1 (S^T), issues the loads of K tile idx+3 and
+    // V tile idx+2 and, before the next barrier, waits for the loads issued one iteration earlier
+    // (K tile idx+2, V tile idx+1).  K tile p is last read in the first half of iteration p, V tile p in
+    // the first half of iteration p+1, so both rings are four stages deep.
     for (int idx = 1; idx < n_iter; ++idx) {
         v_prv = v_cur;
-        bump(k_cur, NSK); bump(k_nxt, NSK); bump(k_ld, NSK); bump(v_cur, NSV); bump(v_ld, NSV);
+        bump(k_cur, NS); bump(k_nxt, NS); bump(k_ld, NS); bump(v_cur, NS); bump(v_ld, NS);
         msk_cur = msk_nxt;
         msk_nxt = pos_masked(idx + 1);
-        const unsigned tb = tile_offset(idx + 3);
-        __syncthreads();    // tile idx+1 is in LDS for everyone; the stages of tile idx+3 are no longer read
+        tb_v = tb_k;
+        tb_k = tile_offset(idx + 3);
+        __syncthreads();    // the tiles waited for last are in LDS for everyone; the stages loaded next are no longer read
         half_step(s0, s1, pb, pa, kptr(k_cur, 1), kptr(k_nxt, 0), vptr(v_prv, 1), vptr(v_cur, 0), true,
-                  msk_cur, 2 * idx + 1, 0, tb, k_lds + (unsigned)(k_ld * TILE * 2) + wave_lds);
+                  msk_cur, 2 * idx + 1, 0, tb_k, k_lds + (unsigned)(k_ld * TILE * 2) + wave_lds);
         half_step(s1, s0, pa, pb, kptr(k_nxt, 0), kptr(k_nxt, 1), vptr(v_cur, 0), vptr(v_cur, 1), true,
-                  msk_nxt, 2 * idx + 2, 1, tb, v_lds + (unsigned)(v_ld * TILE * 2) + wave_lds);
+                  msk_nxt, 2 * idx + 2, 1, tb_v, v_lds + (unsigned)(v_ld * TILE * 2) + wave_lds);
         dma_wait_older();
     }
     dma_wait_all();     // nothing may still be landing in LDS when the wavefront ends
