@@ -143,6 +143,46 @@ difa_status_t difa_worklist_build(int32_t batch, int32_t heads, const int32_t* h
                                   int32_t capacity, int32_t* n_items_out, int32_t* copy_heads,
                                   int32_t* n_copy_out);
 
+/* ------------------------------------------------------------------ host-side schedule
+ * The attention kernel is persistent: it is launched with one workgroup per compute unit, and each
+ * workgroup walks its own list of segments.  A segment is a work record restricted to a range of the
+ * positions of its visiting order (position p = the p-th key tile the record visits: the tiles of
+ * the first range, then those of the second).  Most segments are whole records; to give every
+ * compute unit the same amount of work, some records are cut into several segments that different
+ * workgroups execute, each leaving an unnormalised partial result (fp32 O, row reference, row sum)
+ * in a scratch slot; a short second kernel merges the slots of a record and writes its rows.
+ */
+typedef struct {
+    int32_t bh, q_tile;          /* as in the record                                                  */
+    int32_t kv0_end, nm0_end, kv1_begin, kv1_end, nm1_begin, nm1_end, window;
+    int32_t pos_begin, pos_end;  /* positions [pos_begin, pos_end) of the record's visiting order      */
+    int32_t part_slot;           /* -1: the segment is the whole record and writes `out`; otherwise
+                                    the scratch slot that receives the partial result                 */
+} difa_segment_t;
+
+typedef struct {
+    int32_t bh, q_tile;          /* the record whose rows are merged                                   */
+    int32_t first_slot, n_parts; /* its partial results sit in slots first_slot .. first_slot+n_parts-1 */
+} difa_merge_item_t;
+
+/*
+ * Distribute records over n_wg workgroups (HOST only, no GPU needed).
+ *   items/n_items   records as difa_worklist_build(..., n_xcd = 1, ...) returns them (any order; records
+ *                   with q_tile < 0 are ignored).
+ *   n_wg, n_xcd     number of workgroups and of accelerator dies; workgroup p runs on die p % n_xcd.
+ *                   n_wg must be a multiple of n_xcd.  Heads are kept on one die (two where a cut between
+ *                   dies falls inside a head) so that a head's K and V stay in that die's L2.
+ *   segs/seg_capacity      receives the segments, grouped by workgroup; wg_begin[n_wg + 1] receives each
+ *                          workgroup's first index into segs (wg_begin[n_wg] = number of segments).
+ *   merges/merge_capacity  receives one entry per record that was cut.
+ *   n_slots_out     number of scratch slots used (at most 2 * n_wg).
+ * Returns DIFA_OK, INVALID_ARG, or ALLOC when a capacity is too small.
+ */
+difa_status_t difa_schedule_build(const difa_work_item_t* items, int32_t n_items, int32_t n_wg, int32_t n_xcd,
+                                  difa_segment_t* segs, int32_t seg_capacity, int32_t* wg_begin,
+                                  int32_t* n_segs_out, difa_merge_item_t* merges, int32_t merge_capacity,
+                                  int32_t* n_merges_out, int32_t* n_slots_out);
+
 /* ------------------------------------------------------------------ measurement hooks
  * With timing enabled the library brackets its attention kernel (not the cache copy) with
  * HIP events on the caller's stream; difa_plan_timing_read waits for the last bracket and

@@ -29,6 +29,16 @@ class difa_work_item_t(ctypes.Structure):
                  "window", "n_tiles")]
 
 
+class difa_segment_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("bh", "q_tile", "kv0_end", "nm0_end", "kv1_begin", "kv1_end", "nm1_begin", "nm1_end",
+                 "window", "pos_begin", "pos_end", "part_slot")]
+
+
+class difa_merge_item_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("bh", "q_tile", "first_slot", "n_parts")]
+
+
 def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2503_22796_amd.build` "
@@ -49,6 +59,8 @@ def _load():
     L.difa_tile_shape.argtypes = [i32, i32, i32p, i32p]
     L.difa_worklist_build.restype = ctypes.c_int
     L.difa_worklist_build.argtypes = [i32, i32, vp, vp, i32, i32, i32, i32, i32, vp, i32, i32p, vp, i32p]
+    L.difa_schedule_build.restype = ctypes.c_int
+    L.difa_schedule_build.argtypes = [vp, i32, i32, i32, vp, i32, vp, i32p, vp, i32, i32p, i32p]
     L.difa_plan_timing_enable.restype = ctypes.c_int
     L.difa_plan_timing_enable.argtypes = [vp, i32]
     L.difa_plan_timing_read.restype = ctypes.c_int
@@ -102,6 +114,29 @@ def difa_worklist_build(batch, heads, head_plan, window, n_text, n_img, bm, bn, 
     arr = np.frombuffer(items, dtype=np.dtype([(n, np.int32) for n, _ in difa_work_item_t._fields_]),
                         count=n_items.value).copy()
     return st, arr, copy_heads[:n_copy.value].copy()
+
+
+def difa_schedule_build(items, n_wg, n_xcd):
+    """items: structured array as difa_worklist_build returns.  Returns (status, segments, wg_begin,
+    merge items, number of scratch slots); the arrays are numpy structured / int32 arrays."""
+    items = np.ascontiguousarray(items)
+    n = len(items)
+    seg_cap, merge_cap = n + 2 * n_wg, 2 * n_wg
+    segs = (difa_segment_t * max(seg_cap, 1))()
+    merges = (difa_merge_item_t * max(merge_cap, 1))()
+    wg_begin = np.zeros(n_wg + 1, dtype=np.int32)
+    n_segs, n_merges, n_slots = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
+    st = lib.difa_schedule_build(items.ctypes.data if n else None, n, n_wg, n_xcd, ctypes.cast(segs, ctypes.c_void_p),
+                                 seg_cap, wg_begin.ctypes.data, ctypes.byref(n_segs),
+                                 ctypes.cast(merges, ctypes.c_void_p), merge_cap, ctypes.byref(n_merges),
+                                 ctypes.byref(n_slots))
+    if st != DIFA_OK:
+        return st, None, None, None, 0
+    sa = np.frombuffer(segs, dtype=np.dtype([(n_, np.int32) for n_, _ in difa_segment_t._fields_]),
+                       count=n_segs.value).copy()
+    ma = np.frombuffer(merges, dtype=np.dtype([(n_, np.int32) for n_, _ in difa_merge_item_t._fields_]),
+                       count=n_merges.value).copy()
+    return st, sa, wg_begin, ma, n_slots.value
 
 
 def difa_plan_create(batch, heads, head_dim, dtype=DIFA_DTYPE_BF16, layout=DIFA_LAYOUT_BHND,

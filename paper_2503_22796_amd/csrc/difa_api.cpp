@@ -20,7 +20,8 @@ struct Slot {
     std::vector<int32_t> key;
     void* h_buf = nullptr;  // pinned host staging: CACHE-head indices, then the work records
     void* d_buf = nullptr;  // device copy
-    int32_t n_items = 0, n_copy = 0;
+    int32_t n_items = 0, n_copy = 0, n_merges = 0;
+    size_t wg_off = 0, segs_off = 0, merges_off = 0, items_off = 0;  // byte offsets inside the buffers
     hipEvent_t uploaded = nullptr;  // recorded after the host-to-device copy
     hipEvent_t last_use = nullptr;  // recorded after the last launch that reads d_buf
     hipStream_t upload_stream = nullptr;
@@ -40,7 +41,14 @@ struct difa_plan {
     float scale;
     int32_t bm, bn;
     int32_t item_capacity;
-    size_t buf_bytes, items_off;   // records start items_off bytes into a slot buffer
+    int32_t n_wg, n_xcd;           // persistent workgroups (one per compute unit), accelerator dies
+    size_t buf_bytes, heads_bytes; // slot buffer: cached-head list, then the schedule
+    float* part_o = nullptr;       // device scratch for records cut into pieces: 2 * n_wg slots
+    float* part_ml = nullptr;
+    hipEvent_t last_launch = nullptr;   // after the last attention launch (the scratch is shared by all calls)
+    hipStream_t last_stream = nullptr;
+    bool launched = false;
+    std::vector<difa_work_item_t> recs; // host scratch of the work-list compiler
     Slot slots[kSlots];
     uint64_t clock = 0;
     std::string err;
@@ -172,18 +180,37 @@ extern "C" difa_status_t difa_plan_create(const difa_plan_desc_t* desc, difa_pla
     p->scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)desc->head_dim);
     difa_tile_shape(desc->head_dim, desc->dtype, &p->bm, &p->bn);
     const int64_t q_tiles = ((int64_t)desc->max_tokens + p->bm - 1) / p->bm;
-    const int64_t cap = (int64_t)desc->batch * desc->heads * q_tiles * kXcd;   // padded queues: at most kXcd x the records
-    if (cap > (int64_t)1 << 26) {
+    const int64_t cap = (int64_t)desc->batch * desc->heads * q_tiles;
+    if (cap > (int64_t)1 << 24) {
         delete p;
         return fail(nullptr, DIFA_ERR_UNSUPPORTED, "batch*heads*query tiles exceeds the work-list limit");
     }
     p->item_capacity = (int32_t)cap;
-    p->items_off = ((size_t)desc->heads * sizeof(int32_t) + 63) / 64 * 64;
-    p->buf_bytes = p->items_off + (size_t)cap * sizeof(difa_work_item_t);
+    p->n_wg = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
+    p->n_xcd = p->n_wg % kXcd == 0 ? kXcd : 1;
+    p->heads_bytes = ((size_t)desc->heads * sizeof(int32_t) + 63) / 64 * 64;
+    // worst case: every record whole plus two pieces per workgroup, one merge entry per workgroup
+    p->buf_bytes = p->heads_bytes + ((size_t)p->n_wg + 1) * sizeof(int32_t) + 64 +
+                   ((size_t)cap + 2 * (size_t)p->n_wg) * sizeof(difa_segment_t) + 64 +
+                   2 * (size_t)p->n_wg * sizeof(difa_merge_item_t) + 64 + (size_t)cap * sizeof(difa_work_item_t);
+    p->recs.resize((size_t)cap);
 
     DeviceGuard guard;
     e = guard.enter(desc->device);
     if (e != hipSuccess) { delete p; return fail(nullptr, DIFA_ERR_HIP, hip_msg("hipSetDevice", e)); }
+    if (desc->dtype == DIFA_DTYPE_BF16) {
+        const size_t slots = 2 * (size_t)p->n_wg;
+        e = hipMalloc((void**)&p->part_o, slots * (size_t)p->bm * desc->head_dim * sizeof(float));
+        if (e == hipSuccess) e = hipMalloc((void**)&p->part_ml, slots * (size_t)p->bm * 2 * sizeof(float));
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&p->last_launch, hipEventDisableTiming);
+        if (e != hipSuccess) {
+            if (p->part_o) (void)hipFree(p->part_o);
+            if (p->part_ml) (void)hipFree(p->part_ml);
+            delete p;
+            return fail(nullptr, e == hipErrorOutOfMemory ? DIFA_ERR_ALLOC : DIFA_ERR_HIP,
+                        hip_msg("allocating the scratch for cut records", e));
+        }
+    }
     for (int s = 0; s < kSlots; ++s) {
         Slot& sl = p->slots[s];
         e = hipHostMalloc(&sl.h_buf, p->buf_bytes, hipHostMallocDefault);
@@ -192,6 +219,9 @@ extern "C" difa_status_t difa_plan_create(const difa_plan_desc_t* desc, difa_pla
         if (e == hipSuccess) e = hipEventCreateWithFlags(&sl.last_use, hipEventDisableTiming);
         if (e != hipSuccess) {
             for (int t = 0; t <= s; ++t) free_slot(p->slots[t]);
+            if (p->part_o) (void)hipFree(p->part_o);
+            if (p->part_ml) (void)hipFree(p->part_ml);
+            if (p->last_launch) (void)hipEventDestroy(p->last_launch);
             delete p;
             return fail(nullptr, e == hipErrorOutOfMemory ? DIFA_ERR_ALLOC : DIFA_ERR_HIP,
                         hip_msg("allocating work-list buffers", e));
@@ -211,6 +241,10 @@ extern "C" difa_status_t difa_plan_destroy(difa_plan_t* p) {
         free_slot(s);
     }
     for (TimingPair& tp : p->pool) { (void)hipEventDestroy(tp.start); (void)hipEventDestroy(tp.stop); }
+    if (p->launched) (void)hipEventSynchronize(p->last_launch);
+    if (p->part_o) (void)hipFree(p->part_o);
+    if (p->part_ml) (void)hipFree(p->part_ml);
+    if (p->last_launch) (void)hipEventDestroy(p->last_launch);
     delete p;
     return DIFA_OK;
 }
@@ -289,15 +323,32 @@ extern "C" difa_status_t difa_joint_attention(difa_plan_t* p, const void* q, con
             if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("waiting for a work list in use", e));
         }
         lru->valid = false;
-        int32_t n_items = 0, n_copy = 0;
-        difa_status_t st = difa_worklist_build(B, H, head_plan, window, n_text, n_img, p->bm, p->bn, kXcd,
-                                               (difa_work_item_t*)((char*)lru->h_buf + p->items_off),
-                                               p->item_capacity, &n_items, (int32_t*)lru->h_buf, &n_copy);
+        int32_t n_items = 0, n_copy = 0, n_segs = 0, n_merges = 0, n_slots = 0;
+        char* hb = (char*)lru->h_buf;
+        difa_status_t st = difa_worklist_build(B, H, head_plan, window, n_text, n_img, p->bm, p->bn, 1,
+                                               p->recs.data(), p->item_capacity, &n_items, (int32_t*)hb, &n_copy);
         if (st != DIFA_OK) return fail(p, st, "work-list compilation failed");
-        e = hipMemcpyAsync(lru->d_buf, lru->h_buf, p->items_off + (size_t)n_items * sizeof(difa_work_item_t),
-                           hipMemcpyHostToDevice, stream);   // only the part in use
+        size_t used = p->heads_bytes;
+        lru->wg_off = lru->segs_off = lru->merges_off = lru->items_off = used;
+        if (p->desc.dtype == DIFA_DTYPE_BF16) {
+            lru->wg_off = used;
+            lru->segs_off = (lru->wg_off + ((size_t)p->n_wg + 1) * sizeof(int32_t) + 63) / 64 * 64;
+            const int32_t seg_cap = n_items + 2 * p->n_wg;
+            lru->merges_off = (lru->segs_off + (size_t)seg_cap * sizeof(difa_segment_t) + 63) / 64 * 64;
+            st = difa_schedule_build(p->recs.data(), n_items, p->n_wg, p->n_xcd, (difa_segment_t*)(hb + lru->segs_off),
+                                     seg_cap, (int32_t*)(hb + lru->wg_off), &n_segs,
+                                     (difa_merge_item_t*)(hb + lru->merges_off), 2 * p->n_wg, &n_merges, &n_slots);
+            if (st != DIFA_OK) return fail(p, st, "scheduling the work list failed");
+            used = lru->merges_off + (size_t)n_merges * sizeof(difa_merge_item_t);
+        } else {
+            lru->items_off = used;
+            memcpy(hb + used, p->recs.data(), (size_t)n_items * sizeof(difa_work_item_t));
+            used += (size_t)n_items * sizeof(difa_work_item_t);
+        }
+        e = hipMemcpyAsync(lru->d_buf, lru->h_buf, used, hipMemcpyHostToDevice, stream);   // only the part in use
         if (e == hipSuccess) e = hipEventRecord(lru->uploaded, stream);
         if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("uploading the work list", e));
+        lru->n_merges = n_merges;
         lru->key = key;
         lru->n_items = n_items;
         lru->n_copy = n_copy;
@@ -339,19 +390,37 @@ extern "C" difa_status_t difa_joint_attention(difa_plan_t* p, const void* q, con
 
     // ---- computed heads
     if (slot->n_items > 0) {
+        const char* db = (const char*)slot->d_buf;
         difa::AttnArgs a{};
         a.q = q; a.k = k; a.v = v; a.out = out;
-        a.items = (const difa_work_item_t*)((const char*)slot->d_buf + p->items_off);
+        a.items = (const difa_work_item_t*)(db + slot->items_off);
+        a.segs = (const difa_segment_t*)(db + slot->segs_off);
+        a.wg_begin = (const int32_t*)(db + slot->wg_off);
+        a.merges = (const difa_merge_item_t*)(db + slot->merges_off);
+        a.part_o = p->part_o;
+        a.part_ml = p->part_ml;
         a.stride_b = sb; a.stride_h = sh; a.stride_n = sn;
         a.heads = H; a.n_tokens = N; a.n_text = n_text;
         a.scale = p->scale;
+        const bool fast = p->desc.dtype == DIFA_DTYPE_BF16;
+        // the scratch for cut records is shared by all calls on this object: order them across streams
+        if (fast && p->launched && p->last_stream != stream) {
+            e = hipStreamWaitEvent(stream, p->last_launch, 0);
+            if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("hipStreamWaitEvent", e));
+        }
         TimingPair tp{};
         if (p->timing && (e = timing_begin(p, stream, 0, &tp)) != hipSuccess)
             return fail(p, DIFA_ERR_HIP, hip_msg("hipEventRecord", e));
-        e = p->desc.dtype == DIFA_DTYPE_BF16 ? difa::launch_attn_bf16(a, D, slot->n_items, stream)
-                                             : difa::launch_attn_f32(a, D, slot->n_items, stream);
+        e = fast ? difa::launch_attn_bf16(a, D, p->n_wg, slot->n_merges, stream)
+                 : difa::launch_attn_f32(a, D, slot->n_items, stream);
         if (p->timing) { (void)hipEventRecord(tp.stop, stream); p->pending.push_back(tp); }
         if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("attention launch", e));
+        if (fast) {
+            e = hipEventRecord(p->last_launch, stream);
+            if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("hipEventRecord", e));
+            p->last_stream = stream;
+            p->launched = true;
+        }
     }
     e = hipEventRecord(slot->last_use, stream);
     if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("hipEventRecord", e));

@@ -16,7 +16,12 @@ struct AttnArgs {
     const void* k;
     const void* v;
     void* out;
-    const difa_work_item_t* items;  // device
+    const difa_work_item_t* items;  // device: one record per workgroup (fp32 debug kernel)
+    const difa_segment_t* segs;     // device: segments grouped by workgroup (bf16 kernel)
+    const int32_t* wg_begin;        // device: first segment of each workgroup, n_wg + 1 entries
+    const difa_merge_item_t* merges;  // device: records cut into pieces
+    float* part_o;                  // device scratch: [slot][kBM][head_dim] unnormalised accumulators
+    float* part_ml;                 // device scratch: [slot][kBM][2] row reference (log2 domain), row sum
     int64_t stride_b, stride_h, stride_n;
     int32_t heads, n_tokens, n_text;
     float scale;  // softmax scale (natural-log domain)
@@ -31,7 +36,7 @@ struct CopyArgs {
 };
 
 // Launchers (defined in difa_kernels.hip).  All enqueue on `stream` and return the launch status.
-hipError_t launch_attn_bf16(const AttnArgs& a, int head_dim, int n_items, hipStream_t stream);
+hipError_t launch_attn_bf16(const AttnArgs& a, int head_dim, int n_wg, int n_merges, hipStream_t stream);
 hipError_t launch_attn_f32(const AttnArgs& a, int head_dim, int n_items, hipStream_t stream);
 hipError_t launch_cache_copy(const CopyArgs& a, hipStream_t stream);
 

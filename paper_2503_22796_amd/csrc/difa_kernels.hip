@@ -102,41 +102,9 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     __shared__ __attribute__((aligned(16))) __bf16 Ksm[NS * TILE];
     __shared__ __attribute__((aligned(16))) __bf16 Vsm[NS * TILE];
 
-    const difa_work_item_t it = a.items[blockIdx.x];
-    if (it.q_tile < 0) return;
-
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
     const int N = a.n_tokens, n_text = a.n_text;
-    const int b = it.bh / a.heads, h = it.bh - b * a.heads;
-    const int64_t base = (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
-    const __bf16* __restrict__ qg = (const __bf16*)a.q + base;
-    const __bf16* __restrict__ kg = (const __bf16*)a.k + base;
-    const __bf16* __restrict__ vg = (const __bf16*)a.v + base;
-    __bf16* __restrict__ og = (__bf16*)a.out + base;
-
-    const int row0 = it.q_tile * kBM + wave * 64;           // first query row of this wavefront
     const float c = a.scale * 1.44269504088896340736f;      // scores are kept in the log2 domain
-
-    // ---- per-lane query rows (two: one per 32-row block), their allowed key ranges, Q operands
-    RowState rs[2];
-    bf16x8 qf[2][KS];
-    int i_raw[2];
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        i_raw[qb] = row0 + 32 * qb + l32;
-        const int i = i_raw[qb] < N ? i_raw[qb] : N - 1;    // rows past the end recompute row N-1
-        int lo, hi;
-        if (it.window < 0 || i < n_text) { lo = 0; hi = N - 1; }
-        else { lo = i - it.window; hi = i + it.window < N - 1 ? i + it.window : N - 1; }
-        rs[qb].lo = lo;
-        rs[qb].span = (unsigned)(hi - lo);                  // key j is in the band iff (unsigned)(j-lo) <= span
-        rs[qb].m = -1.0e30f;                                // finite: exp2(-inf - m) must be 0, not NaN
-        rs[qb].l = 0.f;
-        // B operand of S^T = K Q^T: column = query l32, k-slots 8*half..8*half+7 of each 16-wide step
-        const __bf16* qrow = qg + (int64_t)i * a.stride_n + 8 * half;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = *(const bf16x8*)(qrow + 16 * ks);
-    }
 
     // ---- per-lane LDS offsets (elements, within one stage)
     int koff[KS];                                           // A operand of S^T: row l32, chunk 2*ks+half
@@ -152,39 +120,18 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
         }
     }
 
-    floatx16 o[DB][2];
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[db][qb][r] = 0.f;
-
-    const int n_iter = it.kv0_end + (it.kv1_end - it.kv1_begin);
-    auto tile_of = [&](int idx) {
-        idx = idx < n_iter ? idx : n_iter - 1;              // past the end: reload the last tile (unused)
-        return idx < it.kv0_end ? idx : it.kv1_begin + (idx - it.kv0_end);
-    };
-    auto tile_masked = [&](int idx) {
-        const int t = tile_of(idx);
-        return idx < it.kv0_end ? (t >= it.nm0_end) : (t < it.nm1_begin || t >= it.nm1_end);
-    };
     // ---- global -> LDS: K/V tiles are written into the ring by the load itself
     // (buffer_load_dwordx4 ... lds: lane l of a wavefront deposits its 16 bytes at M0 + 16*l), so a
     // tile never occupies registers and needs no ds_write.  One instruction fills RPI consecutive
     // tile rows; the XOR swizzle of the LDS layout is applied by permuting which 16-byte chunk of the
-    // row each lane fetches.  One buffer descriptor per tensor for this (batch, head): rows past the
-    // last token read as zero (they are masked later).  The loads are outside the compiler's view, so
-    // the wait for them is explicit (dma_wait) and sits just before the barrier that publishes the tile.
+    // row each lane fetches.  One buffer descriptor per tensor for the segment's (batch, head): rows
+    // past the last token read as zero (they are masked later).  The loads are outside the compiler's
+    // view, so the wait for them is explicit (dma_wait) and sits just before the barrier that
+    // publishes the tile.
     constexpr int RPI = 64 / CPR;                           // tile rows per load instruction
     constexpr int NDMA = kBN / RPI / 4;                     // load instructions per wavefront, tensor and tile
     const unsigned head_bytes = (unsigned)(((int64_t)(N - 1) * a.stride_n + D) * 2);
-    uintx4 krsrc, vrsrc;
-    {
-        const unsigned long long ka = (unsigned long long)kg, va = (unsigned long long)vg;
-        krsrc[0] = (unsigned)ka; krsrc[1] = (unsigned)(ka >> 32) & 0xffffu; krsrc[2] = head_bytes; krsrc[3] = 0x00020000u;
-        vrsrc[0] = (unsigned)va; vrsrc[1] = (unsigned)(va >> 32) & 0xffffu; vrsrc[2] = head_bytes; vrsrc[3] = 0x00020000u;
-    }
+    uintx4 krsrc, vrsrc;                                    // descriptors of the head whose tiles are being loaded
     const unsigned wave_u = __builtin_amdgcn_readfirstlane(wave);
     unsigned gk[NDMA], gv[NDMA];                            // per-lane byte offsets inside a tile
 #pragma unroll
@@ -198,7 +145,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     const unsigned v_lds = (unsigned)(unsigned long long)(__attribute__((address_space(3))) __bf16*)Vsm;
     // One load instruction: part u (0..NDMA-1) of a K (tensor 0) or V (tensor 1) tile.  `tb` is the tile's
     // byte offset inside the head, or an offset beyond the buffer for positions past the end of the
-    // record (those fetch nothing and deposit zeros); `dst` is this wavefront's LDS byte address inside
+    // segment (those fetch nothing and deposit zeros); `dst` is this wavefront's LDS byte address inside
     // the ring stage.  All per-tile scalars are computed once per iteration by the caller.
     auto dma_part = [&](int tensor, int u, unsigned tb, unsigned dst) __attribute__((always_inline)) {
         if (tensor == 0)
@@ -209,26 +156,104 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
                          :: "s"(dst + (unsigned)(u * RPI * D * 2)), "v"(gv[u] + tb), "s"(vrsrc));
     };
     const unsigned wave_lds = wave_u * (unsigned)(NDMA * RPI * D * 2);     // this wavefront's rows inside a stage
-    auto tile_offset = [&](int idx) {                       // byte offset of the tile at position idx
-        return idx < n_iter ? (unsigned)tile_of(idx) * tile_bytes : 0x80000000u;
-    };
-    auto dma_tile = [&](int idx, bool with_v) {
-        const unsigned tb = tile_offset(idx);
-        const unsigned kd = k_lds + (unsigned)((idx % NS) * TILE * 2) + wave_lds;
-        const unsigned vd = v_lds + (unsigned)((idx % NS) * TILE * 2) + wave_lds;
-#pragma unroll
-        for (int u = 0; u < NDMA; ++u) {
-            dma_part(0, u, tb, kd);
-            if (with_v) dma_part(1, u, tb, vd);
-        }
-    };
-    // all loads done / all but the 2*NDMA youngest (= the tile issued during the current iteration) done
+    // all loads done / all but the 2*NDMA youngest (= the tiles issued during the current iteration) done
     auto dma_wait_all = [] { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
     auto dma_wait_older = [] { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * NDMA) : "memory"); };
 
+    // What a segment needs before its first block: its K tiles 0..2 and V tiles 0, 1 in the ring (the
+    // segment's tile p goes to stage (sb + p) % 4) and its query rows in the Q operand registers.
+    // Requested ahead of time: for the first segment at once, for every other one by its predecessor,
+    // between the end of its own key loop and its epilogue.
+    bf16x8 qf[2][KS];
+    auto first_loads = [&](const difa_segment_t& sg, int sb) __attribute__((always_inline)) {
+        const int b = sg.bh / a.heads, h = sg.bh - b * a.heads;
+        const int64_t base = (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
+        const unsigned long long ka = (unsigned long long)((const __bf16*)a.k + base);
+        const unsigned long long va = (unsigned long long)((const __bf16*)a.v + base);
+        krsrc[0] = (unsigned)ka; krsrc[1] = (unsigned)(ka >> 32) & 0xffffu; krsrc[2] = head_bytes; krsrc[3] = 0x00020000u;
+        vrsrc[0] = (unsigned)va; vrsrc[1] = (unsigned)(va >> 32) & 0xffffu; vrsrc[2] = head_bytes; vrsrc[3] = 0x00020000u;
+        const int n = sg.pos_end - sg.pos_begin;
+#pragma unroll
+        for (int t = 0; t < 3; ++t) {
+            const int p = sg.pos_begin + t;
+            const int tile = p < sg.kv0_end ? p : sg.kv1_begin + (p - sg.kv0_end);
+            const unsigned tb = t < n ? (unsigned)tile * tile_bytes : 0x80000000u;
+            const unsigned st = (unsigned)(((sb + t) & 3) * TILE * 2) + wave_lds;
+#pragma unroll
+            for (int u = 0; u < NDMA; ++u) {
+                dma_part(0, u, tb, k_lds + st);
+                if (t < 2) dma_part(1, u, tb, v_lds + st);
+            }
+        }
+        const __bf16* qg = (const __bf16*)a.q + base;
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            const int i_r = sg.q_tile * kBM + wave * 64 + 32 * qb + l32;
+            const int i = i_r < N ? i_r : N - 1;            // rows past the end recompute row N-1
+            // B operand of S^T = K Q^T: column = query l32, k-slots 8*half..8*half+7 of each 16-wide step
+            const __bf16* qrow = qg + (int64_t)i * a.stride_n + 8 * half;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = *(const bf16x8*)(qrow + 16 * ks);
+        }
+    };
+
+    // Persistent workgroup: one per compute unit, walking the segments the host scheduled for it.
+    // The record of the following segment is fetched while the current one runs.
+    const int seg_end = __builtin_amdgcn_readfirstlane(a.wg_begin[blockIdx.x + 1]);
+    const int seg_first = __builtin_amdgcn_readfirstlane(a.wg_begin[blockIdx.x]);
+    if (seg_first >= seg_end) return;
+    difa_segment_t seg_next = a.segs[seg_first];
+    int sbase = 0;                                          // ring stage of the current segment's tile 0
+    first_loads(seg_next, sbase);
+    for (int seg_idx = seg_first; seg_idx < seg_end; ++seg_idx) {
+    const difa_segment_t it = seg_next;
+
+    const int b = it.bh / a.heads, h = it.bh - b * a.heads;
+    __bf16* __restrict__ og = (__bf16*)a.out + (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
+    const int row0 = it.q_tile * kBM + wave * 64;           // first query row of this wavefront
+
+    // ---- per-lane query rows (two: one per 32-row block) and their allowed key ranges
+    RowState rs[2];
+    int i_raw[2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        i_raw[qb] = row0 + 32 * qb + l32;
+        const int i = i_raw[qb] < N ? i_raw[qb] : N - 1;
+        int lo, hi;
+        if (it.window < 0 || i < n_text) { lo = 0; hi = N - 1; }
+        else { lo = i - it.window; hi = i + it.window < N - 1 ? i + it.window : N - 1; }
+        rs[qb].lo = lo;
+        rs[qb].span = (unsigned)(hi - lo);                  // key j is in the band iff (unsigned)(j-lo) <= span
+        rs[qb].m = -1.0e30f;                                // finite: exp2(-inf - m) must be 0, not NaN
+        rs[qb].l = 0.f;
+    }
+
+    floatx16 o[DB][2];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[db][qb][r] = 0.f;
+
+    // The segment covers positions [pos_begin, pos_end) of the record's visiting order; idx counts from
+    // the segment's first position.
+    const int n_iter = it.pos_end - it.pos_begin;
+    auto tile_of = [&](int idx) {
+        const int p = it.pos_begin + (idx < n_iter ? idx : n_iter - 1);   // past the end: reload the last tile (unused)
+        return p < it.kv0_end ? p : it.kv1_begin + (p - it.kv0_end);
+    };
+    auto tile_masked = [&](int idx) {
+        const int t = tile_of(idx);
+        return it.pos_begin + idx < it.kv0_end ? (t >= it.nm0_end) : (t < it.nm1_begin || t >= it.nm1_end);
+    };
+    auto tile_offset = [&](int idx) {                       // byte offset of the tile at position idx
+        return idx < n_iter ? (unsigned)tile_of(idx) * tile_bytes : 0x80000000u;
+    };
+
     // ---- S^T = K Q^T for one 32-key block jb of a tile: s[qb], register r = key 32*jb + 8*(r/4) + 4*half + r%4
     auto qk_block = [&](int idx, int jb, floatx16 (&s)[2]) {
-        const __bf16* kst = &Ksm[(idx % NS) * TILE + 32 * jb * D];
+        const __bf16* kst = &Ksm[((idx + sbase) & 3) * TILE + 32 * jb * D];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const bf16x8 ka = *(const bf16x8*)(kst + koff[ks]);
@@ -296,7 +321,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     // reference; the block's weights and row sums are recomputed, the running sums and O are scaled.
     // The accumulators live in accumulation registers and are scaled in place there; the waits cover
     // MFMA results still in flight.
-    auto renormalise = [&](const floatx16 (&sc)[2], float (&mneg)[2], float (&lb)[2], bf16x8 (&pw)[2][2]) __attribute__((always_inline)) {
+    auto renormalise = [&](const floatx16 (&sc)[2], float (&mneg)[2], float (&lb)[2], bf16x8 (&pw)[2][2], bool rescale_o) __attribute__((always_inline)) {
         float alpha[2];
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
@@ -325,6 +350,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
                 lb[qb] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, lb[qb], false);
             }
         }
+        if (!rescale_o) return;     // nothing has been accumulated yet
         asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 #pragma unroll
         for (int db = 0; db < DB; ++db)
@@ -350,10 +376,15 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     };
 
     // ---- prologue: tiles 0 and 1 into the ring, S^T of block (tile 0, jb 0)
-    dma_tile(0, true);
-    dma_tile(1, true);
-    dma_tile(2, false);
-    dma_wait_all();
+    dma_wait_all();     // the segment's first tiles and query rows, requested ahead of time
+    // The assembly MFMAs read Q from accumulation registers.  If the compiler holds the loaded rows in
+    // ordinary registers, this is where it has to move them over: a vector write needs two wait states
+    // before a matrix instruction reads it, and only here are those guaranteed.
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[qb][ks]));
+    asm volatile("s_nop 1" ::: "memory");
     __syncthreads();
 
     // The pipeline advances by 32-key blocks g = 2*tile + jb.  One half-step for block g is one basic
@@ -408,7 +439,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
             __builtin_amdgcn_sched_barrier(0);
         }
         if (__builtin_expect(__builtin_amdgcn_ballot_w64(fmaxf(lb[0], lb[1]) > kTrip) != 0, 0))
-            renormalise(s_cur, mneg, lb, p_cur);
+            renormalise(s_cur, mneg, lb, p_cur, with_pv);
         rs[0].l += lb[0];
         rs[1].l += lb[1];
         // block number blk_nxt = 2*position + jb; its first key is only needed on this rare path
@@ -418,21 +449,22 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
         }
     };
 
+    seg_next = a.segs[seg_idx + 1 < seg_end ? seg_idx + 1 : seg_idx];   // has the whole key loop to arrive
     qk_block(0, 0, s0);
     if (tile_masked(0)) mask_block(tile_of(0) * kBN, s0);   // (before the loop-carried flags exist)
 
     // Loop-carried scalars (all uniform over the wavefront), advanced once per iteration instead of
     // being recomputed from the position: ring stages of the tiles in use, mask flags, load target.
     // With one wavefront per SIMD nothing hides scalar work, so there is as little of it as possible.
-    const int m0e = it.nm0_end < it.kv0_end ? it.nm0_end : it.kv0_end;          // positions [0, m0e) and
-    const int m1b = it.kv0_end + (it.nm1_begin > it.kv1_begin ? it.nm1_begin - it.kv1_begin : 0);
-    const int m1e = it.kv0_end + ((it.nm1_end < it.kv1_end ? it.nm1_end : it.kv1_end) - it.kv1_begin);
+    const int m0e = (it.nm0_end < it.kv0_end ? it.nm0_end : it.kv0_end) - it.pos_begin;   // idx in [.., m0e) and
+    const int m1b = it.kv0_end + (it.nm1_begin > it.kv1_begin ? it.nm1_begin - it.kv1_begin : 0) - it.pos_begin;
+    const int m1e = it.kv0_end + ((it.nm1_end < it.kv1_end ? it.nm1_end : it.kv1_end) - it.kv1_begin) - it.pos_begin;
     auto pos_masked = [&](int idx) { return !(idx < m0e || (idx >= m1b && idx < m1e)); };   // [m1b, m1e) are mask-free
     auto bump = [](int& st, int n) { st = st + 1 == n ? 0 : st + 1; };
     auto kptr = [&](int st, int jb) { return &Ksm[st * TILE + 32 * jb * D]; };
     auto vptr = [&](int st, int jb) { return &Vsm[st * TILE + 32 * jb * D]; };
-    int k_cur = 0, k_nxt = 1, k_ld = 3;                     // K stages of positions idx, idx+1, idx+3
-    int v_prv = 0, v_cur = 0, v_ld = 2;                     // V stages of positions idx-1, idx, idx+2
+    int k_cur = sbase & 3, k_nxt = (sbase + 1) & 3, k_ld = (sbase + 3) & 3;   // K stages of positions idx, idx+1, idx+3
+    int v_prv = k_cur, v_cur = k_cur, v_ld = (sbase + 2) & 3;                  // V stages of positions idx-1, idx, idx+2
     bool msk_cur = pos_masked(0), msk_nxt = pos_masked(1);
     unsigned tb_k = tile_offset(3), tb_v = tile_offset(2);  // tiles whose K / V loads the coming iteration issues
 
@@ -463,7 +495,13 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
                   msk_nxt, 2 * idx + 2, 1, tb_v, v_lds + (unsigned)(v_ld * TILE * 2) + wave_lds);
         dma_wait_older();
     }
-    dma_wait_all();     // nothing may still be landing in LDS when the wavefront ends
+    // The key loop is over: the K stages and all V stages but the last tile's are free.  Loads past the
+    // segment's end may still be depositing zeros, and other wavefronts may still be reading: wait for
+    // both, then request what the next segment needs first, so that it arrives during the epilogue.
+    dma_wait_all();
+    __syncthreads();
+    const int sbase_next = (sbase + n_iter) & 3;            // keeps clear of the stage the last P V still reads
+    if (seg_idx + 1 < seg_end) first_loads(seg_next, sbase_next);
     // P V of the very last block (its first operands are already in flight)
     {
         const __bf16* vst = vptr(v_cur, 1);
@@ -477,33 +515,101 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     }
 
     // ---- epilogue: O^T register r of block db is feature d = 32*db + 8*(r/4) + 4*half + r%4
+    if (it.part_slot < 0) {
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        const float l_tot = halves_sum(rs[qb].l);
-        const float inv = 1.0f / l_tot;
-        if (i_raw[qb] < N) {
-            __bf16* orow = og + (int64_t)i_raw[qb] * a.stride_n;
+        for (int qb = 0; qb < 2; ++qb) {
+            const float l_tot = halves_sum(rs[qb].l);
+            const float inv = 1.0f / l_tot;
+            if (i_raw[qb] < N) {
+                __bf16* orow = og + (int64_t)i_raw[qb] * a.stride_n;
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+                for (int db = 0; db < DB; ++db)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    bf16x4 w4;
+                    for (int g = 0; g < 4; ++g) {
+                        bf16x4 w4;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) w4[e] = (__bf16)(o[db][qb][4 * g + e] * inv);
-                    *(bf16x4*)(orow + 32 * db + 8 * g + 4 * half) = w4;
-                }
+                        for (int e = 0; e < 4; ++e) w4[e] = (__bf16)(o[db][qb][4 * g + e] * inv);
+                        *(bf16x4*)(orow + 32 * db + 8 * g + 4 * half) = w4;
+                    }
+            }
         }
+    } else {
+        // a piece of a record: the unnormalised fp32 accumulators, the row reference (log2 domain)
+        // and the row sum go to the piece's scratch slot; merge_parts_kernel combines the pieces
+        float* po = a.part_o + (int64_t)it.part_slot * (kBM * D);
+        float* pml = a.part_ml + (int64_t)it.part_slot * (kBM * 2);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            const float l_tot = halves_sum(rs[qb].l);
+            const int rl = wave * 64 + 32 * qb + l32;        // row inside the query tile
+            if (i_raw[qb] < N) {
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        floatx4 w4;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) w4[e] = o[db][qb][4 * g + e];
+                        *(floatx4*)(po + rl * D + 32 * db + 8 * g + 4 * half) = w4;
+                    }
+                if (half == 0) {
+                    floatx2 ml;
+                    ml[0] = rs[qb].m;
+                    ml[1] = l_tot;
+                    *(floatx2*)(pml + rl * 2) = ml;
+                }
+            }
+        }
+    }
+    sbase = sbase_next;
     }
 }
 
-hipError_t launch_attn_bf16(const AttnArgs& a, int head_dim, int n_items, hipStream_t stream) {
-    if (n_items <= 0) return hipSuccess;
-    if (head_dim == 128)
-        hipLaunchKernelGGL(attn_bf16_kernel<128>, dim3(n_items), dim3(256), 0, stream, a);
-    else if (head_dim == 64)
-        hipLaunchKernelGGL(attn_bf16_kernel<64>, dim3(n_items), dim3(256), 0, stream, a);
-    else
+// Rows of a record that was cut into pieces: out = sum_p O_p 2^(m_p - M) / sum_p l_p 2^(m_p - M),
+// M = max_p m_p.  One workgroup per record, one thread per (row, 8-feature chunk) in turn.
+template <int D>
+__global__ __launch_bounds__(256) void merge_parts_kernel(AttnArgs a) {
+    const difa_merge_item_t mi = a.merges[blockIdx.x];
+    const int b = mi.bh / a.heads, h = mi.bh - b * a.heads;
+    __bf16* og = (__bf16*)a.out + (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
+    constexpr int CH = D / 8;
+    for (int e = threadIdx.x; e < kBM * CH; e += 256) {
+        const int rl = e / CH, ch = e - rl * CH;
+        const int i = mi.q_tile * kBM + rl;
+        if (i >= a.n_tokens) continue;
+        float M = -INFINITY;
+        for (int p = 0; p < mi.n_parts; ++p)
+            M = fmaxf(M, a.part_ml[((int64_t)(mi.first_slot + p) * kBM + rl) * 2]);
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, l = 0.f;
+        for (int p = 0; p < mi.n_parts; ++p) {
+            const int64_t slot = mi.first_slot + p;
+            const floatx2 ml = *(const floatx2*)(a.part_ml + (slot * kBM + rl) * 2);
+            const float w = __builtin_amdgcn_exp2f(ml[0] - M);
+            l = fmaf(ml[1], w, l);
+            const float* src = a.part_o + (slot * kBM + rl) * D + 8 * ch;
+            const floatx4 x0 = *(const floatx4*)src, x1 = *(const floatx4*)(src + 4);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) { acc[t] = fmaf(x0[t], w, acc[t]); acc[4 + t] = fmaf(x1[t], w, acc[4 + t]); }
+        }
+        const float inv = 1.0f / l;
+        bf16x8 w8;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) w8[t] = (__bf16)(acc[t] * inv);
+        *(bf16x8*)(og + (int64_t)i * a.stride_n + 8 * ch) = w8;
+    }
+}
+
+hipError_t launch_attn_bf16(const AttnArgs& a, int head_dim, int n_wg, int n_merges, hipStream_t stream) {
+    if (n_wg <= 0) return hipSuccess;
+    if (head_dim == 128) {
+        hipLaunchKernelGGL(attn_bf16_kernel<128>, dim3(n_wg), dim3(256), 0, stream, a);
+        if (n_merges > 0) hipLaunchKernelGGL(merge_parts_kernel<128>, dim3(n_merges), dim3(256), 0, stream, a);
+    } else if (head_dim == 64) {
+        hipLaunchKernelGGL(attn_bf16_kernel<64>, dim3(n_wg), dim3(256), 0, stream, a);
+        if (n_merges > 0) hipLaunchKernelGGL(merge_parts_kernel<64>, dim3(n_merges), dim3(256), 0, stream, a);
+    } else {
         return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 

@@ -188,3 +188,149 @@ extern "C" difa_status_t difa_worklist_build(int32_t batch, int32_t heads, const
     std::copy(recs.begin(), recs.end(), items);
     return DIFA_OK;
 }
+
+// ------------------------------------------------------------------------------------------
+// Records -> per-workgroup segment lists for the persistent attention kernel.
+//
+// The hardware dispatcher would hand whole records to compute units as they free up; with records
+// of a few hundred key tiles each, the last round leaves most of the chip idle (1584 equal records on
+// 256 compute units: 6.19 rounds cost 7).  Here the distribution is computed on the host instead:
+// whole records are dealt out in order to the least loaded workgroup of their die (which keeps the
+// workgroups of a die on neighbouring query tiles of one head, marching through its K/V together),
+// and the records that no longer fit under the die's average load are cut along their key-tile
+// positions into pieces that fill the workgroups up to that average.
+// ------------------------------------------------------------------------------------------
+namespace {
+
+constexpr int kSegOverhead = 10;  // cost of starting a segment, in key-tile iterations
+constexpr int kMinPiece = 8;      // shortest piece worth cutting off a record
+
+difa_segment_t whole_segment(const difa_work_item_t& r) {
+    difa_segment_t s{};
+    s.bh = r.bh; s.q_tile = r.q_tile;
+    s.kv0_end = r.kv0_end; s.nm0_end = r.nm0_end;
+    s.kv1_begin = r.kv1_begin; s.kv1_end = r.kv1_end;
+    s.nm1_begin = r.nm1_begin; s.nm1_end = r.nm1_end;
+    s.window = r.window;
+    s.pos_begin = 0; s.pos_end = r.n_tiles;
+    s.part_slot = -1;
+    return s;
+}
+
+}  // namespace
+
+extern "C" difa_status_t difa_schedule_build(const difa_work_item_t* items, int32_t n_items, int32_t n_wg,
+                                             int32_t n_xcd, difa_segment_t* segs, int32_t seg_capacity,
+                                             int32_t* wg_begin, int32_t* n_segs_out, difa_merge_item_t* merges,
+                                             int32_t merge_capacity, int32_t* n_merges_out, int32_t* n_slots_out) {
+    if (n_items < 0 || (n_items > 0 && !items) || n_wg < 1 || n_xcd < 1 || n_wg % n_xcd != 0 || !wg_begin ||
+        !n_segs_out || !n_merges_out || !n_slots_out || seg_capacity < 0 || merge_capacity < 0 ||
+        (seg_capacity > 0 && !segs) || (merge_capacity > 0 && !merges))
+        return DIFA_ERR_INVALID_ARG;
+    std::vector<difa_work_item_t> recs;
+    for (int32_t i = 0; i < n_items; ++i) {
+        if (items[i].q_tile < 0) continue;
+        if (items[i].n_tiles < 1) return DIFA_ERR_INVALID_ARG;
+        recs.push_back(items[i]);
+    }
+    std::stable_sort(recs.begin(), recs.end(), [](const difa_work_item_t& a, const difa_work_item_t& b) {
+        return a.bh != b.bh ? a.bh < b.bh : a.q_tile < b.q_tile;
+    });
+    // heads in order of decreasing cost, the whole sequence cut into n_xcd runs of equal cost
+    struct HeadSpan { size_t first, count; int64_t cost; };
+    std::vector<HeadSpan> spans;
+    for (size_t i = 0; i < recs.size();) {
+        size_t j = i;
+        int64_t cost = 0;
+        while (j < recs.size() && recs[j].bh == recs[i].bh) { cost += recs[j].n_tiles + kSegOverhead; ++j; }
+        spans.push_back({i, j - i, cost});
+        i = j;
+    }
+    std::stable_sort(spans.begin(), spans.end(), [](const HeadSpan& a, const HeadSpan& b) { return a.cost > b.cost; });
+    int64_t total = 0;
+    for (const HeadSpan& sp : spans) total += sp.cost;
+    std::vector<std::vector<difa_work_item_t>> die((size_t)n_xcd);
+    int64_t cum = 0;
+    for (const HeadSpan& sp : spans)
+        for (size_t k = 0; k < sp.count; ++k) {
+            const difa_work_item_t& r = recs[sp.first + k];
+            const int64_t c = r.n_tiles + kSegOverhead;
+            int64_t x = total > 0 ? ((2 * cum + c) * n_xcd) / (2 * total) : 0;
+            x = std::min<int64_t>(std::max<int64_t>(x, 0), n_xcd - 1);
+            die[(size_t)x].push_back(r);
+            cum += c;
+        }
+
+    const int per_die = n_wg / n_xcd;
+    const int slot_capacity = 2 * n_wg;
+    std::vector<std::vector<difa_segment_t>> lists((size_t)n_wg);
+    std::vector<difa_merge_item_t> merge_list;
+    int n_slots = 0;
+    for (int x = 0; x < n_xcd; ++x) {
+        std::vector<difa_work_item_t>& q = die[(size_t)x];
+        // longest records first (a query tile that holds text rows visits every key tile), in classes of
+        // 16 key tiles so that the records of one head, which differ by a tile or two, stay neighbours
+        std::stable_sort(q.begin(), q.end(), [](const difa_work_item_t& a, const difa_work_item_t& b) {
+            return a.n_tiles / 16 > b.n_tiles / 16;
+        });
+        std::vector<int64_t> load((size_t)per_die, 0);
+        auto least = [&]() { return (int)(std::min_element(load.begin(), load.end()) - load.begin()); };
+        auto wg_of = [&](int w) -> std::vector<difa_segment_t>& { return lists[(size_t)(w * n_xcd + x)]; };
+        int64_t die_cost = 0;
+        for (const difa_work_item_t& r : q) die_cost += r.n_tiles + kSegOverhead;
+        // every workgroup is expected to take one extra piece
+        const int64_t target = (die_cost + (int64_t)per_die * kSegOverhead + per_die - 1) / per_die;
+        std::vector<difa_work_item_t> pool;
+        for (const difa_work_item_t& r : q) {
+            const int w = least();
+            const int64_t c = r.n_tiles + kSegOverhead;
+            if (load[(size_t)w] + c <= target) {
+                wg_of(w).push_back(whole_segment(r));
+                load[(size_t)w] += c;
+            } else {
+                pool.push_back(r);
+            }
+        }
+        for (const difa_work_item_t& r : pool) {
+            std::vector<std::pair<int, difa_segment_t>> pieces;
+            int pos = 0;
+            while (pos < r.n_tiles) {
+                const int w = least();
+                const int remaining = r.n_tiles - pos;
+                const int64_t room = target - load[(size_t)w] - kSegOverhead;
+                int take = remaining;
+                const bool may_cut = n_slots + (int)pieces.size() + 2 <= slot_capacity;
+                if (may_cut && room >= kMinPiece && room < remaining) {
+                    take = (int)room;
+                    if (remaining - take < kMinPiece) take = remaining;
+                }
+                difa_segment_t s = whole_segment(r);
+                s.pos_begin = pos;
+                s.pos_end = pos + take;
+                pieces.push_back({w, s});
+                load[(size_t)w] += take + kSegOverhead;
+                pos += take;
+            }
+            if (pieces.size() > 1) {
+                difa_merge_item_t m{r.bh, r.q_tile, n_slots, (int32_t)pieces.size()};
+                for (auto& pc : pieces) pc.second.part_slot = n_slots++;
+                merge_list.push_back(m);
+            }
+            for (auto& pc : pieces) wg_of(pc.first).push_back(pc.second);
+        }
+    }
+    int64_t n_segs = 0;
+    for (const auto& l : lists) n_segs += (int64_t)l.size();
+    *n_segs_out = (int32_t)n_segs;
+    *n_merges_out = (int32_t)merge_list.size();
+    *n_slots_out = n_slots;
+    if (n_segs > seg_capacity || (int64_t)merge_list.size() > merge_capacity) return DIFA_ERR_ALLOC;
+    int32_t at = 0;
+    for (int w = 0; w < n_wg; ++w) {
+        wg_begin[w] = at;
+        for (const difa_segment_t& s : lists[(size_t)w]) segs[at++] = s;
+    }
+    wg_begin[n_wg] = at;
+    std::copy(merge_list.begin(), merge_list.end(), merges);
+    return DIFA_OK;
+}
