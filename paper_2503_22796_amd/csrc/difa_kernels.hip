@@ -206,7 +206,21 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     int sbase = 0;                                          // ring stage of the current segment's tile 0
     first_loads(seg_next, sbase);
     for (int seg_idx = seg_first; seg_idx < seg_end; ++seg_idx) {
-    const difa_segment_t it = seg_next;
+    // (the record was read with vector loads; moving its fields to scalar registers tells the compiler
+    // that everything derived from them is uniform over the wavefront)
+    difa_segment_t it;
+    it.bh = __builtin_amdgcn_readfirstlane(seg_next.bh);
+    it.q_tile = __builtin_amdgcn_readfirstlane(seg_next.q_tile);
+    it.kv0_end = __builtin_amdgcn_readfirstlane(seg_next.kv0_end);
+    it.nm0_end = __builtin_amdgcn_readfirstlane(seg_next.nm0_end);
+    it.kv1_begin = __builtin_amdgcn_readfirstlane(seg_next.kv1_begin);
+    it.kv1_end = __builtin_amdgcn_readfirstlane(seg_next.kv1_end);
+    it.nm1_begin = __builtin_amdgcn_readfirstlane(seg_next.nm1_begin);
+    it.nm1_end = __builtin_amdgcn_readfirstlane(seg_next.nm1_end);
+    it.window = __builtin_amdgcn_readfirstlane(seg_next.window);
+    it.pos_begin = __builtin_amdgcn_readfirstlane(seg_next.pos_begin);
+    it.pos_end = __builtin_amdgcn_readfirstlane(seg_next.pos_end);
+    it.part_slot = __builtin_amdgcn_readfirstlane(seg_next.part_slot);
 
     const int b = it.bh / a.heads, h = it.bh - b * a.heads;
     __bf16* __restrict__ og = (__bf16*)a.out + (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
@@ -265,7 +279,39 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
         }
         mfma_results_visible();
     };
+    // Element mask of one 32-key block whose first key is j0.  The host marks a tile as masked when any
+    // of the workgroup's 256 rows has a forbidden key in it; for the 64 rows of one wavefront most such
+    // blocks lie entirely inside the band, or are cut by one band edge only.  That is decided here from
+    // scalars, so that the common cases cost nothing or one compare per score.
+    const int row_first = it.q_tile * kBM + (int)wave_u * 64;              // this wavefront's rows (uniform)
+    const int row_last = row_first + 63 < N - 1 ? row_first + 63 : N - 1;
     auto mask_block = [&](int j0, floatx16 (&s)[2]) {
+        const bool plain = j0 >= n_text && row_first >= n_text && j0 + 31 < N && it.window >= 0;
+        if (plain) {
+            // image rows, image keys, no tail: row i allows keys [i - w, i + w]
+            const bool low = row_last - it.window > j0;                    // some row's band starts after j0
+            const bool high = row_first + it.window < j0 + 31;             // some row's band ends before the block does
+            if (!low && !high) return;
+            // key offset inside the block (8*(r/4) + r%4, a constant per register) against the row's edge
+            if (low && !high) {
+#pragma unroll
+                for (int qb = 0; qb < 2; ++qb) {
+                    const int edge = rs[qb].lo - j0 - 4 * half;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) s[qb][r] = 8 * (r >> 2) + (r & 3) >= edge ? s[qb][r] : -INFINITY;
+                }
+                return;
+            }
+            if (high && !low) {
+#pragma unroll
+                for (int qb = 0; qb < 2; ++qb) {
+                    const int edge = rs[qb].lo + (int)rs[qb].span - j0 - 4 * half;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) s[qb][r] = 8 * (r >> 2) + (r & 3) <= edge ? s[qb][r] : -INFINITY;
+                }
+                return;
+            }
+        }
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
