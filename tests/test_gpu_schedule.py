@@ -1,0 +1,80 @@
+"""A denoising schedule through the C ABI: per-layer plan objects and ping-pong output/cache
+buffers that persist across steps, a new per-head plan at every (layer, step), step 0 all full
+and cached heads only afterwards (Sec. 3.2: a cached head re-emits the previous step's output;
+Sec. 3.4.2: the plan is indexed by step, layer and head).  Reduced to a few layers and steps;
+the shapes are the FLUX-like 2K layer and a small odd-sized one."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2503_22796_amd import workloads as W
+from util import ARROW, CACHE, TOL_BF16, boundary_rows
+
+pytestmark = pytest.mark.gpu
+
+
+def run_schedule(base, layers, steps, hp, win, rows):
+    from oracle import difa_oracle as O
+    from paper_2503_22796_amd import binding as B
+    dev = torch.device("cuda:0")
+    shape = (base.B, base.H, base.N, base.D)
+    plans = [B.difa_plan_create(base.B, base.H, base.D, max_tokens=base.N) for _ in range(layers)]
+    bufs = [[torch.full(shape, float("nan"), dtype=torch.bfloat16, device=dev) for _ in range(2)]
+            for _ in range(layers)]
+    prev_host = [None] * layers
+    worst = 0.0
+    try:
+        for t in range(steps):
+            q, k, v = W.make_qkv(base, step=t)
+            qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)
+            for l in range(layers):
+                out, cache = bufs[l][(t + 1) % 2], bufs[l][t % 2]
+                out.fill_(float("nan"))
+                B.difa_joint_attention(plans[l], qd, kd, vd, out, cache if t > 0 else None, hp[l, t],
+                                       base.n_text, base.n_img, win[l, t])
+            torch.cuda.synchronize()
+            for l in range(layers):
+                got = bufs[l][(t + 1) % 2].cpu()
+                ref, _, _ = O.joint_attention(q, k, v, prev_host[l], hp[l, t], win[l, t], base.n_text, base.n_img,
+                                              rows=rows)
+                for h in range(base.H):
+                    if hp[l, t, h] == CACHE:      # every row, bit for bit, from this layer's previous output
+                        assert t > 0
+                        assert torch.equal(got[:, h].view(torch.int16), prev_host[l][:, h].view(torch.int16)), \
+                            f"layer {l} step {t} head {h}: cached head differs from the previous step"
+                    else:
+                        g = got[:, h][:, rows].double()
+                        assert torch.isfinite(got[:, h].float()).all(), f"layer {l} step {t} head {h}: unwritten rows"
+                        err = float((g - ref[:, h]).abs().max())
+                        assert err <= TOL_BF16, f"layer {l} step {t} head {h}: max abs err {err:.3e}"
+                        worst = max(worst, err)
+                prev_host[l] = got
+    finally:
+        for p in plans:
+            B.difa_plan_destroy(p)
+    return worst
+
+
+def test_flux_2k_schedule_three_steps_two_layers():
+    base = W.flux_2k_mixed()
+    hp, win = W.schedule_plans(57, 28, base.H, seed=5)
+    assert (hp[:, 0] == 0).all() and (hp[:, 1:] == CACHE).any()
+    layers, steps = [0, 33], 3
+    rows = boundary_rows(base.n_text, base.n_img, [512, 1024, 2048], extra=24, seed=9)
+    worst = run_schedule(base, len(layers), steps, hp[layers], win[layers], rows)
+    print(f"flux_2k schedule ({len(layers)} layers x {steps} steps): max_abs_err={worst:.3e}", flush=True)
+
+
+def test_small_schedule_many_plans_per_layer():
+    # more distinct plans per layer than the plan object memoises, an odd token count, head_dim 64
+    H, layers, steps = 6, 3, 11
+    base = W.Workload("small_schedule", 2, H, 64, 37, 484, np.zeros(H, np.int32), np.zeros(H, np.int32), seed=77)
+    rng = np.random.Generator(np.random.PCG64(78))
+    hp = np.zeros((layers, steps, H), np.int32)
+    win = np.zeros((layers, steps, H), np.int32)
+    for l in range(layers):
+        for t in range(1, steps):
+            hp[l, t] = rng.integers(0, 3, size=H)
+            win[l, t] = np.where(hp[l, t] == ARROW, rng.integers(0, 500, size=H), 0)
+    worst = run_schedule(base, layers, steps, hp, win, list(range(base.N)))
+    print(f"small schedule: max_abs_err={worst:.3e}", flush=True)

@@ -130,3 +130,87 @@ def test_invalid_plans_are_rejected():
     assert st == B.DIFA_ERR_INVALID_ARG
     st, _, _ = B.difa_worklist_build(1, 1, [FULL], [0], 0, 0, 8, 4)
     assert st == B.DIFA_ERR_INVALID_ARG
+
+
+# ----------------------------------------------------------------------------- the schedule
+def _schedule(wl_args, n_wg, n_xcd):
+    batch, H, hp, win, n_text, n_img, bm, bn = wl_args
+    st, items, _ = B.difa_worklist_build(batch, H, hp, win, n_text, n_img, bm, bn, 1)
+    assert st == B.DIFA_OK
+    st, segs, wg_begin, merges, n_slots = B.difa_schedule_build(items, n_wg, n_xcd)
+    assert st == B.DIFA_OK
+    return items, segs, wg_begin, merges, n_slots
+
+
+def _check_schedule(items, segs, wg_begin, merges, n_slots, n_wg, n_xcd):
+    # the per-workgroup lists partition the segment array
+    assert wg_begin[0] == 0 and wg_begin[n_wg] == len(segs)
+    assert all(wg_begin[w] <= wg_begin[w + 1] for w in range(n_wg))
+    # every (record, position) is covered exactly once, and a segment repeats its record's fields
+    by_key = {(int(r["bh"]), int(r["q_tile"])): r for r in items}
+    cover = {k: np.zeros(int(r["n_tiles"]), dtype=np.int32) for k, r in by_key.items()}
+    pieces = {}
+    for s in segs:
+        k = (int(s["bh"]), int(s["q_tile"]))
+        r = by_key[k]
+        for f in ("kv0_end", "nm0_end", "kv1_begin", "kv1_end", "nm1_begin", "nm1_end", "window"):
+            assert s[f] == r[f]
+        assert 0 <= s["pos_begin"] < s["pos_end"] <= r["n_tiles"]
+        cover[k][s["pos_begin"]:s["pos_end"]] += 1
+        whole = s["pos_begin"] == 0 and s["pos_end"] == r["n_tiles"]
+        assert (s["part_slot"] < 0) == whole
+        if not whole:
+            pieces.setdefault(k, []).append(int(s["part_slot"]))
+    for k, c in cover.items():
+        assert (c == 1).all(), f"record {k} is not covered exactly once"
+    # the merge list names exactly the cut records and their slots; slots are used once
+    assert len(merges) == len(pieces)
+    used = []
+    for m in merges:
+        k = (int(m["bh"]), int(m["q_tile"]))
+        slots = sorted(pieces[k])
+        assert m["n_parts"] == len(slots) >= 2
+        assert slots == list(range(int(m["first_slot"]), int(m["first_slot"]) + len(slots)))
+        used += slots
+    assert sorted(used) == list(range(n_slots)) and n_slots <= 2 * n_wg
+    # a head's segments sit on at most two dies
+    die_of = {}
+    for w in range(n_wg):
+        for s in segs[wg_begin[w]:wg_begin[w + 1]]:
+            die_of.setdefault(int(s["bh"]), set()).add(w % n_xcd)
+    assert all(len(d) <= 2 for d in die_of.values())
+
+
+@pytest.mark.parametrize("n_wg,n_xcd", [(8, 1), (16, 8), (256, 8), (6, 3)])
+@pytest.mark.parametrize("n_text,n_img,heads", [
+    (512, 4096, [(FULL, 0)] * 3 + [(ARROW, 128), (ARROW, 1024), (CACHE, 0)]),
+    (333, 1000, [(ARROW, 7), (FULL, 0), (ARROW, 500)]),
+    (0, 64, [(ARROW, 3)]),
+    (16, 64, [(FULL, 0), (ARROW, 8), (ARROW, 16), (CACHE, 0)]),
+])
+def test_schedule_covers_every_position_once(n_wg, n_xcd, n_text, n_img, heads):
+    hp, win = [m for m, _ in heads], [w for _, w in heads]
+    args = (2, len(heads), hp, win, n_text, n_img, 256, 64)
+    items, segs, wg_begin, merges, n_slots = _schedule(args, n_wg, n_xcd)
+    _check_schedule(items, segs, wg_begin, merges, n_slots, n_wg, n_xcd)
+
+
+def test_schedule_of_the_2k_layers_is_balanced():
+    from paper_2503_22796_amd import workloads as W
+    for wl, bound in ((W.flux_2k_full(), 1.04), (W.flux_2k_mixed(), 1.12)):
+        args = (wl.B, wl.H, wl.head_plan, wl.window, wl.n_text, wl.n_img, 256, 64)
+        items, segs, wg_begin, merges, n_slots = _schedule(args, 256, 8)
+        _check_schedule(items, segs, wg_begin, merges, n_slots, 256, 8)
+        load = np.array([(segs["pos_end"][wg_begin[w]:wg_begin[w + 1]] -
+                          segs["pos_begin"][wg_begin[w]:wg_begin[w + 1]]).sum() for w in range(256)])
+        ideal = items["n_tiles"].sum() / 256
+        assert load.max() <= bound * ideal, (wl.name, load.max(), ideal)
+        assert len(merges) > 0           # the tail records are cut
+
+
+def test_schedule_rejects_bad_arguments():
+    st, items, _ = B.difa_worklist_build(1, 1, [FULL], [0], 4, 60, 256, 64, 1)
+    assert B.difa_schedule_build(items, 12, 8)[0] == B.DIFA_ERR_INVALID_ARG      # n_wg not a multiple of n_xcd
+    assert B.difa_schedule_build(items, 0, 1)[0] == B.DIFA_ERR_INVALID_ARG
+    st, segs, wg_begin, merges, n_slots = B.difa_schedule_build(items[:0], 8, 8)
+    assert st == B.DIFA_OK and len(segs) == 0 and n_slots == 0 and (wg_begin == 0).all()
