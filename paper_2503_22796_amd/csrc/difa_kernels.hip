@@ -344,7 +344,9 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
         pin(x[0]);
         pin(x[1]);
     };
-    auto softmax_b = [&](int s, float (&x)[2], float (&lb)[2], bf16x8 (&pw)[2][2]) __attribute__((always_inline)) {
+    // (the row-sum update of a pair trails its conversion by one slot: a dot product issued right after
+    // the conversion it reads costs a wait state, as does a conversion right after its exponential)
+    auto softmax_b = [&](int s, float (&x)[2], float (&lb)[2], bf16x8 (&pw)[2][2], unsigned& held) __attribute__((always_inline)) {
         const int qb = s >> 3, r = 2 * (s & 7);
         bf16x2 ones;
         ones[0] = (__bf16)1.0f;
@@ -352,14 +354,18 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
         floatx2 pf;
         pf[0] = x[0];
         pf[1] = __builtin_amdgcn_exp2f(x[1]);
-        bf16x2 pr = __builtin_convertvector(pf, bf16x2);             // the weights that enter P V ...
+        if (s > 0) {                                                  // the weights that entered P V are the ones summed
+            const int qp = (s - 1) >> 3;
+            lb[qp] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, held), ones, ((s - 1) & 7) ? lb[qp] : 0.f, false);
+            pin(lb[qp]);
+        }
+        bf16x2 pr = __builtin_convertvector(pf, bf16x2);
         unsigned bits = __builtin_bit_cast(unsigned, pr);
         asm volatile("" : "+v"(bits));
         pr = __builtin_bit_cast(bf16x2, bits);
         pw[qb][r >> 3][r & 7] = pr[0];
         pw[qb][r >> 3][(r & 7) + 1] = pr[1];
-        lb[qb] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, lb[qb], false);   // ... are the ones summed
-        pin(lb[qb]);
+        held = bits;
     };
     // Rare side path, uniform over the wavefront: some row of block g produced a weight beyond 2^kTrip
     // (always the case for the first block, whose rows still carry the initial reference).  Every row
@@ -455,7 +461,8 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
                          bf16x8 (&p_cur)[2][2], const __bf16* kst_nxt, const __bf16* kst_after,
                          const __bf16* vst_prev, const __bf16* vst_cur, bool with_pv, bool mask_nxt,
                          int blk_nxt, int dma_tensor, unsigned dma_tb, unsigned dma_dst) __attribute__((always_inline)) {
-        float mneg[2] = {-rs[0].m, -rs[1].m}, lb[2] = {0.f, 0.f};
+        float mneg[2] = {-rs[0].m, -rs[1].m}, lb[2];
+        unsigned held = 0;
 #pragma unroll
         for (int s = 0; s < 16; ++s) {
             const int j = s >> 1, qb = s & 1, jn = j + AHEAD;    // operand jn is fetched while operand j is used
@@ -478,11 +485,17 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
                     else vq[jn - NOP] = v_operand(vst_cur, jn - NOP);
                 }
             }
-            softmax_b(s, x, lb, p_cur);
+            softmax_b(s, x, lb, p_cur, held);
             // the loads of a later tile are spread over the slots (a burst of them right after the
             // barrier stalls all four wavefronts on the one memory pipe)
             if ((s & 3) == 1 && (s >> 2) < NDMA) dma_part(dma_tensor, s >> 2, dma_tb, dma_dst);
             __builtin_amdgcn_sched_barrier(0);
+        }
+        {
+            bf16x2 ones;
+            ones[0] = (__bf16)1.0f;
+            ones[1] = (__bf16)1.0f;
+            lb[1] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, held), ones, lb[1], false);
         }
         if (__builtin_expect(__builtin_amdgcn_ballot_w64(fmaxf(lb[0], lb[1]) > kTrip) != 0, 0))
             renormalise(s_cur, mneg, lb, p_cur, with_pv);
@@ -506,11 +519,12 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     const int m1b = it.kv0_end + (it.nm1_begin > it.kv1_begin ? it.nm1_begin - it.kv1_begin : 0) - it.pos_begin;
     const int m1e = it.kv0_end + ((it.nm1_end < it.kv1_end ? it.nm1_end : it.kv1_end) - it.kv1_begin) - it.pos_begin;
     auto pos_masked = [&](int idx) { return !(idx < m0e || (idx >= m1b && idx < m1e)); };   // [m1b, m1e) are mask-free
-    auto bump = [](int& st, int n) { st = st + 1 == n ? 0 : st + 1; };
-    auto kptr = [&](int st, int jb) { return &Ksm[st * TILE + 32 * jb * D]; };
-    auto vptr = [&](int st, int jb) { return &Vsm[st * TILE + 32 * jb * D]; };
-    int k_cur = sbase & 3, k_nxt = (sbase + 1) & 3, k_ld = (sbase + 3) & 3;   // K stages of positions idx, idx+1, idx+3
-    int v_prv = k_cur, v_cur = k_cur, v_ld = (sbase + 2) & 3;                  // V stages of positions idx-1, idx, idx+2
+    auto bump = [](int& off) { off = (off + TILE) & (NS * TILE - 1); };          // next ring stage (element offset)
+    auto kptr = [&](int off, int jb) { return &Ksm[off + 32 * jb * D]; };
+    auto vptr = [&](int off, int jb) { return &Vsm[off + 32 * jb * D]; };
+    // ring stages as element offsets: K stages of positions idx, idx+1, idx+3, V stages of idx-1, idx, idx+2
+    int k_cur = (sbase & 3) * TILE, k_nxt = ((sbase + 1) & 3) * TILE, k_ld = ((sbase + 3) & 3) * TILE;
+    int v_prv = k_cur, v_cur = k_cur, v_ld = ((sbase + 2) & 3) * TILE;
     bool msk_cur = pos_masked(0), msk_nxt = pos_masked(1);
     unsigned tb_k = tile_offset(3), tb_v = tile_offset(2);  // tiles whose K / V loads the coming iteration issues
 
@@ -518,9 +532,9 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
     for (int j = 0; j < AHEAD; ++j) kq[j] = k_operand(kptr(k_cur, 1), j);
     half_step(s0, s1, pb, pa, kptr(k_cur, 1), kptr(k_nxt, 0), vptr(v_cur, 0), vptr(v_cur, 0), false,
-              msk_cur, 1, 0, tb_k, k_lds + (unsigned)(k_ld * TILE * 2) + wave_lds);
+              msk_cur, 1, 0, tb_k, k_lds + (unsigned)(k_ld * 2) + wave_lds);
     half_step(s1, s0, pa, pb, kptr(k_nxt, 0), kptr(k_nxt, 1), vptr(v_cur, 0), vptr(v_cur, 1), true,
-              msk_nxt, 2, 1, tb_v, v_lds + (unsigned)(v_ld * TILE * 2) + wave_lds);
+              msk_nxt, 2, 1, tb_v, v_lds + (unsigned)(v_ld * 2) + wave_lds);
     dma_wait_older();
 
     // Iteration idx works on tiles idx-1 (P V), idx and idx+1 (S^T), issues the loads of K tile idx+3 and
@@ -529,16 +543,16 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     // the first half of iteration p+1, so both rings are four stages deep.
     for (int idx = 1; idx < n_iter; ++idx) {
         v_prv = v_cur;
-        bump(k_cur, NS); bump(k_nxt, NS); bump(k_ld, NS); bump(v_cur, NS); bump(v_ld, NS);
+        bump(k_cur); bump(k_nxt); bump(k_ld); bump(v_cur); bump(v_ld);
         msk_cur = msk_nxt;
         msk_nxt = pos_masked(idx + 1);
         tb_v = tb_k;
         tb_k = tile_offset(idx + 3);
         __syncthreads();    // the tiles waited for last are in LDS for everyone; the stages loaded next are no longer read
         half_step(s0, s1, pb, pa, kptr(k_cur, 1), kptr(k_nxt, 0), vptr(v_prv, 1), vptr(v_cur, 0), true,
-                  msk_cur, 2 * idx + 1, 0, tb_k, k_lds + (unsigned)(k_ld * TILE * 2) + wave_lds);
+                  msk_cur, 2 * idx + 1, 0, tb_k, k_lds + (unsigned)(k_ld * 2) + wave_lds);
         half_step(s1, s0, pa, pb, kptr(k_nxt, 0), kptr(k_nxt, 1), vptr(v_cur, 0), vptr(v_cur, 1), true,
-                  msk_nxt, 2 * idx + 2, 1, tb_v, v_lds + (unsigned)(v_ld * TILE * 2) + wave_lds);
+                  msk_nxt, 2 * idx + 2, 1, tb_v, v_lds + (unsigned)(v_ld * 2) + wave_lds);
         dma_wait_older();
     }
     // The key loop is over: the K stages and all V stages but the last tile's are free.  Loads past the
