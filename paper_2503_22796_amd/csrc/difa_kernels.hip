@@ -293,12 +293,21 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
             const bool high = row_first + it.window < j0 + 31;             // some row's band ends before the block does
             if (!low && !high) return;
             // key offset inside the block (8*(r/4) + r%4, a constant per register) against the row's edge
+            // (compare and select written out so that the scores are replaced where they are, two
+            // instructions per score; the wait states are what a vector write of VCC needs before a
+            // vector instruction reads it)
+            const float ninf = -INFINITY;
             if (low && !high) {
 #pragma unroll
                 for (int qb = 0; qb < 2; ++qb) {
                     const int edge = rs[qb].lo - j0 - 4 * half;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) s[qb][r] = 8 * (r >> 2) + (r & 3) >= edge ? s[qb][r] : -INFINITY;
+                    for (int r = 0; r < 16; ++r) {
+                        float x = s[qb][r];
+                        asm volatile("v_cmp_gt_i32 vcc, %1, %2\n\ts_nop 1\n\tv_cndmask_b32 %0, %0, %3, vcc"
+                                     : "+v"(x) : "v"(edge), "n"(8 * (r >> 2) + (r & 3)), "v"(ninf) : "vcc");
+                        s[qb][r] = x;
+                    }
                 }
                 return;
             }
@@ -307,7 +316,12 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
                 for (int qb = 0; qb < 2; ++qb) {
                     const int edge = rs[qb].lo + (int)rs[qb].span - j0 - 4 * half;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) s[qb][r] = 8 * (r >> 2) + (r & 3) <= edge ? s[qb][r] : -INFINITY;
+                    for (int r = 0; r < 16; ++r) {
+                        float x = s[qb][r];
+                        asm volatile("v_cmp_lt_i32 vcc, %1, %2\n\ts_nop 1\n\tv_cndmask_b32 %0, %0, %3, vcc"
+                                     : "+v"(x) : "v"(edge), "n"(8 * (r >> 2) + (r & 3)), "v"(ninf) : "vcc");
+                        s[qb][r] = x;
+                    }
                 }
                 return;
             }

@@ -202,8 +202,32 @@ extern "C" difa_status_t difa_worklist_build(int32_t batch, int32_t heads, const
 // ------------------------------------------------------------------------------------------
 namespace {
 
-constexpr int kSegOverhead = 10;  // cost of starting a segment, in key-tile iterations
-constexpr int kMinPiece = 8;      // shortest piece worth cutting off a record
+// Cost model of a segment, in quarter key-tile iterations (measured on MI355X: a plain iteration takes
+// about 3700 clocks, one whose two blocks go through the element mask up to 5500; the fixed cost of a
+// segment -- first tiles, a slower first iteration, drain, epilogue -- is about four iterations, and
+// a sweep of this constant on the 2K layers put the best balance at ten).
+constexpr int kUnit = 4;                  // cost units per key-tile iteration
+constexpr int kMaskedExtra = 2;           // extra units of an iteration on a masked tile
+constexpr int kSegOverhead = 10 * kUnit;  // starting and finishing a segment, the slower first iteration included
+constexpr int kMinPiece = 8;              // shortest piece (in key tiles) worth cutting off a record
+
+// Masked tiles among positions [p0, p1) of a record's visiting order.
+int masked_between(const difa_work_item_t& r, int p0, int p1) {
+    int n = 0;
+    const int e0 = std::min(p1, r.kv0_end);
+    if (p0 < e0) n += std::max(0, e0 - std::max(p0, std::min(r.nm0_end, r.kv0_end)));
+    const int b1 = std::max(p0, r.kv0_end);
+    if (b1 < p1) {
+        const int a = r.kv1_begin + (b1 - r.kv0_end), b = r.kv1_begin + (p1 - r.kv0_end);
+        const int free = std::max(0, std::min(b, r.nm1_end) - std::max(a, r.nm1_begin));
+        n += (b - a) - free;
+    }
+    return n;
+}
+
+int64_t range_cost(const difa_work_item_t& r, int p0, int p1) {
+    return (int64_t)kUnit * (p1 - p0) + (int64_t)kMaskedExtra * masked_between(r, p0, p1) + kSegOverhead;
+}
 
 difa_segment_t whole_segment(const difa_work_item_t& r) {
     difa_segment_t s{};
@@ -242,7 +266,7 @@ extern "C" difa_status_t difa_schedule_build(const difa_work_item_t* items, int3
     for (size_t i = 0; i < recs.size();) {
         size_t j = i;
         int64_t cost = 0;
-        while (j < recs.size() && recs[j].bh == recs[i].bh) { cost += recs[j].n_tiles + kSegOverhead; ++j; }
+        while (j < recs.size() && recs[j].bh == recs[i].bh) { cost += range_cost(recs[j], 0, recs[j].n_tiles); ++j; }
         spans.push_back({i, j - i, cost});
         i = j;
     }
@@ -254,7 +278,7 @@ extern "C" difa_status_t difa_schedule_build(const difa_work_item_t* items, int3
     for (const HeadSpan& sp : spans)
         for (size_t k = 0; k < sp.count; ++k) {
             const difa_work_item_t& r = recs[sp.first + k];
-            const int64_t c = r.n_tiles + kSegOverhead;
+            const int64_t c = range_cost(r, 0, r.n_tiles);
             int64_t x = total > 0 ? ((2 * cum + c) * n_xcd) / (2 * total) : 0;
             x = std::min<int64_t>(std::max<int64_t>(x, 0), n_xcd - 1);
             die[(size_t)x].push_back(r);
@@ -277,13 +301,13 @@ extern "C" difa_status_t difa_schedule_build(const difa_work_item_t* items, int3
         auto least = [&]() { return (int)(std::min_element(load.begin(), load.end()) - load.begin()); };
         auto wg_of = [&](int w) -> std::vector<difa_segment_t>& { return lists[(size_t)(w * n_xcd + x)]; };
         int64_t die_cost = 0;
-        for (const difa_work_item_t& r : q) die_cost += r.n_tiles + kSegOverhead;
+        for (const difa_work_item_t& r : q) die_cost += range_cost(r, 0, r.n_tiles);
         // every workgroup is expected to take one extra piece
         const int64_t target = (die_cost + (int64_t)per_die * kSegOverhead + per_die - 1) / per_die;
         std::vector<difa_work_item_t> pool;
         for (const difa_work_item_t& r : q) {
             const int w = least();
-            const int64_t c = r.n_tiles + kSegOverhead;
+            const int64_t c = range_cost(r, 0, r.n_tiles);
             if (load[(size_t)w] + c <= target) {
                 wg_of(w).push_back(whole_segment(r));
                 load[(size_t)w] += c;
@@ -297,7 +321,7 @@ extern "C" difa_status_t difa_schedule_build(const difa_work_item_t* items, int3
             while (pos < r.n_tiles) {
                 const int w = least();
                 const int remaining = r.n_tiles - pos;
-                const int64_t room = target - load[(size_t)w] - kSegOverhead;
+                const int64_t room = (target - load[(size_t)w] - kSegOverhead) / kUnit;   // in key tiles
                 int take = remaining;
                 const bool may_cut = n_slots + (int)pieces.size() + 2 <= slot_capacity;
                 if (may_cut && room >= kMinPiece && room < remaining) {
@@ -308,7 +332,7 @@ extern "C" difa_status_t difa_schedule_build(const difa_work_item_t* items, int3
                 s.pos_begin = pos;
                 s.pos_end = pos + take;
                 pieces.push_back({w, s});
-                load[(size_t)w] += take + kSegOverhead;
+                load[(size_t)w] += range_cost(r, pos, pos + take);
                 pos += take;
             }
             if (pieces.size() > 1) {

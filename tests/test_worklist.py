@@ -173,12 +173,15 @@ def _check_schedule(items, segs, wg_begin, merges, n_slots, n_wg, n_xcd):
         assert slots == list(range(int(m["first_slot"]), int(m["first_slot"]) + len(slots)))
         used += slots
     assert sorted(used) == list(range(n_slots)) and n_slots <= 2 * n_wg
-    # a head's segments sit on at most two dies
+    # heads are kept together: a head lies on the dies its share of the work spans, plus one for the cuts
     die_of = {}
     for w in range(n_wg):
         for s in segs[wg_begin[w]:wg_begin[w + 1]]:
             die_of.setdefault(int(s["bh"]), set()).add(w % n_xcd)
-    assert all(len(d) <= 2 for d in die_of.values())
+    total = float(items["n_tiles"].sum())
+    for bh, dies in die_of.items():
+        share = float(items["n_tiles"][items["bh"] == bh].sum()) / total * n_xcd
+        assert len(dies) <= int(np.ceil(share * 1.5)) + 1, (bh, dies, share)
 
 
 @pytest.mark.parametrize("n_wg,n_xcd", [(8, 1), (16, 8), (256, 8), (6, 3)])
