@@ -640,15 +640,19 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
 }
 
 // Rows of a record that was cut into pieces: out = sum_p O_p 2^(m_p - M) / sum_p l_p 2^(m_p - M),
-// M = max_p m_p.  One workgroup per record, one thread per (row, 8-feature chunk) in turn.
+// M = max_p m_p.  kMergeSplit workgroups per record, one thread per (row, 8-feature chunk): the few
+// records that are cut are spread over the whole chip, and the reads of a row are 16-byte vectors.
+constexpr int kMergeSplit = 8;
 template <int D>
 __global__ __launch_bounds__(256) void merge_parts_kernel(AttnArgs a) {
-    const difa_merge_item_t mi = a.merges[blockIdx.x];
+    const difa_merge_item_t mi = a.merges[blockIdx.x / kMergeSplit];
     const int b = mi.bh / a.heads, h = mi.bh - b * a.heads;
     __bf16* og = (__bf16*)a.out + (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
     constexpr int CH = D / 8;
-    for (int e = threadIdx.x; e < kBM * CH; e += 256) {
-        const int rl = e / CH, ch = e - rl * CH;
+    constexpr int ROWS = kBM / kMergeSplit;
+    const int row_base = (blockIdx.x % kMergeSplit) * ROWS;
+    for (int e = threadIdx.x; e < ROWS * CH; e += 256) {
+        const int rl = row_base + e / CH, ch = e % CH;
         const int i = mi.q_tile * kBM + rl;
         if (i >= a.n_tokens) continue;
         float M = -INFINITY;
@@ -677,10 +681,10 @@ hipError_t launch_attn_bf16(const AttnArgs& a, int head_dim, int n_wg, int n_mer
     if (n_wg <= 0) return hipSuccess;
     if (head_dim == 128) {
         hipLaunchKernelGGL(attn_bf16_kernel<128>, dim3(n_wg), dim3(256), 0, stream, a);
-        if (n_merges > 0) hipLaunchKernelGGL(merge_parts_kernel<128>, dim3(n_merges), dim3(256), 0, stream, a);
+        if (n_merges > 0) hipLaunchKernelGGL(merge_parts_kernel<128>, dim3(n_merges * kMergeSplit), dim3(256), 0, stream, a);
     } else if (head_dim == 64) {
         hipLaunchKernelGGL(attn_bf16_kernel<64>, dim3(n_wg), dim3(256), 0, stream, a);
-        if (n_merges > 0) hipLaunchKernelGGL(merge_parts_kernel<64>, dim3(n_merges), dim3(256), 0, stream, a);
+        if (n_merges > 0) hipLaunchKernelGGL(merge_parts_kernel<64>, dim3(n_merges * kMergeSplit), dim3(256), 0, stream, a);
     } else {
         return hipErrorInvalidValue;
     }
