@@ -590,22 +590,42 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
 
     // ---- epilogue: O^T register r of block db is feature d = 32*db + 8*(r/4) + 4*half + r%4
     if (it.part_slot < 0) {
+        // A lane holds features 8g + 4*half + (0..3) of its row for g = 0..3 in each block db.  The two
+        // halves of the wavefront exchange one quad per pair (g, g+1), after which the lower half holds
+        // features 8g..8g+7 and the upper half 8(g+1)..8(g+1)+7: 16-byte stores, half as many of them (with
+        // the next segment's loads already in flight, more memory instructions than the 63 the counter
+        // can track would stall the wavefront until loads return).
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             const float l_tot = halves_sum(rs[qb].l);
             const float inv = 1.0f / l_tot;
-            if (i_raw[qb] < N) {
-                __bf16* orow = og + (int64_t)i_raw[qb] * a.stride_n;
+            __bf16* orow = og + (int64_t)(i_raw[qb] < N ? i_raw[qb] : N - 1) * a.stride_n;
 #pragma unroll
-                for (int db = 0; db < DB; ++db)
+            for (int db = 0; db < DB; ++db)
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        bf16x4 w4;
+                for (int gp = 0; gp < 2; ++gp) {
+                    unsigned w[2][2];                        // [g - 2*gp][pair of features]
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) w4[e] = (__bf16)(o[db][qb][4 * g + e] * inv);
-                        *(bf16x4*)(orow + 32 * db + 8 * g + 4 * half) = w4;
+                    for (int gg = 0; gg < 2; ++gg)
+#pragma unroll
+                        for (int e2 = 0; e2 < 2; ++e2) {
+                            floatx2 f;
+                            f[0] = o[db][qb][4 * (2 * gp + gg) + 2 * e2] * inv;
+                            f[1] = o[db][qb][4 * (2 * gp + gg) + 2 * e2 + 1] * inv;
+                            w[gg][e2] = __builtin_bit_cast(unsigned, __builtin_convertvector(f, bf16x2));
+                        }
+                    uintx4 q4;
+#pragma unroll
+                    for (int e2 = 0; e2 < 2; ++e2) {
+                        // lower half keeps its quad of g and receives the upper half's; the upper half receives
+                        // the lower half's quad of g+1 and keeps its own
+                        const auto r = __builtin_amdgcn_permlane32_swap(w[0][e2], w[1][e2], false, false);
+                        const unsigned first = r[0], second = r[1];
+                        q4[e2] = first;
+                        q4[2 + e2] = second;
                     }
-            }
+                    if (i_raw[qb] < N) *(uintx4*)(orow + 32 * db + 16 * gp + 8 * half) = q4;
+                }
         }
     } else {
         // a piece of a record: the unnormalised fp32 accumulators, the row reference (log2 domain)
