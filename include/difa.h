@@ -40,6 +40,12 @@ typedef enum {
 enum { DIFA_HEAD_FULL = 0, DIFA_HEAD_ARROW = 1, DIFA_HEAD_CACHE = 2 };
 enum { DIFA_DTYPE_BF16 = 0, DIFA_DTYPE_F32 = 1 }; /* F32 = slow all-fp32 debug path */
 enum { DIFA_LAYOUT_BHND = 0, DIFA_LAYOUT_BNHD = 1 };
+/* Plan flags.  DIFA_FLAG_BLOCK_BAND selects the block-granular band of the paper's own kernel
+ * (Sec. 3.3, Fig. 4: a block that mixes kept and discarded pairs is computed as a dense block, so
+ * that only the sequence tail needs masking): an ARROW head then attends to every pair of a (query
+ * tile, key tile) block of difa_tile_shape() rows x keys that holds at least one pair of the exact
+ * arrow pattern.  Without the flag the band is exact, pair by pair. */
+enum { DIFA_FLAG_BLOCK_BAND = 1u };
 
 /* Static description of a layer's attention call; fixed for the life of a plan object. */
 typedef struct {
@@ -51,7 +57,7 @@ typedef struct {
     int32_t max_tokens;    /* upper bound on n_text + n_img of any later call (>= 1)       */
     float   softmax_scale; /* 0 selects 1/sqrt(head_dim)                                   */
     int32_t device;        /* HIP device ordinal                                           */
-    uint32_t flags;        /* reserved, must be 0                                          */
+    uint32_t flags;        /* DIFA_FLAG_* bits; unknown bits are rejected                   */
 } difa_plan_desc_t;
 
 /*
@@ -61,7 +67,7 @@ typedef struct {
  *   desc      HOST pointer, read during the call only.
  *   plan_out  HOST pointer; receives the object.  The object owns small device and pinned
  *             host buffers (compiled work lists), sized from desc->max_tokens.
- * Errors: INVALID_ARG (NULL, sizes < 1, flags != 0), UNSUPPORTED (head_dim not 64/128,
+ * Errors: INVALID_ARG (NULL, sizes < 1, unknown flag bits), UNSUPPORTED (head_dim not 64/128,
  * unknown dtype/layout, device is not gfx950), ALLOC, HIP.  On error *plan_out is NULL.
  */
 difa_status_t difa_plan_create(const difa_plan_desc_t* desc, difa_plan_t** plan_out);
@@ -131,6 +137,8 @@ int32_t difa_tile_shape(int32_t head_dim, int32_t dtype, int32_t* bm, int32_t* b
  *                   whose workgroup p runs on accelerator die p % n_xcd (each with its own L2):
  *                   n_xcd interleaved queues of equal total cost, heads kept together on a die,
  *                   short queues padded with records whose q_tile is -1.
+ *   flags           DIFA_FLAG_BLOCK_BAND: ARROW records visit the same key tiles but carry window -1 and
+ *                   need the in-tile mask on the sequence tail only.
  *   items/capacity  HOST array to fill (may be NULL with capacity 0 to only count).
  *   n_items_out     number of records, padding included (written also when capacity is short).
  *   copy_heads/n_copy_out  optional: int32[heads] receiving the indices of CACHE heads.
@@ -139,7 +147,7 @@ int32_t difa_tile_shape(int32_t head_dim, int32_t dtype, int32_t* bm, int32_t* b
  */
 difa_status_t difa_worklist_build(int32_t batch, int32_t heads, const int32_t* head_plan,
                                   const int32_t* window, int32_t n_text, int32_t n_img,
-                                  int32_t bm, int32_t bn, int32_t n_xcd, difa_work_item_t* items,
+                                  int32_t bm, int32_t bn, int32_t n_xcd, uint32_t flags, difa_work_item_t* items,
                                   int32_t capacity, int32_t* n_items_out, int32_t* copy_heads,
                                   int32_t* n_copy_out);
 

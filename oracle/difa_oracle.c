@@ -23,6 +23,12 @@
  * not allowed contributes nothing": each row is score -> max -> exp -> sum ->
  * weighted mean, in that order, in double precision.
  *
+ * Block-granular band (Sec. 3.3 and Fig. 4: the paper's kernel turns a block that mixes kept
+ * and discarded pairs into a dense block): with block sizes (bm, bn) given, an ARROW head
+ * attends to pair (i, j) iff the block of bm query rows and bn keys that holds it contains at
+ * least one pair of the exact pattern above.  The block table is filled from that sentence as
+ * it stands: every pair of the exact pattern marks its block.
+ *
  * Readings of points the paper leaves open (text tokens first; w is a half-width,
  * inclusive; 1-D band on the flattened image index; scale given by the caller)
  * are listed with their reasons in the repository's design notes.
@@ -63,6 +69,20 @@ int difa_oracle_allowed(int mode, int i, int j, int n_text, int w)
     return abs(i - j) <= w;                /* visual-to-visual: local band    */
 }
 
+/* Sec. 3.3 / Fig. 4: blocks[(i / bm) * n_kb + j / bn] = 1 iff the block holds a pair the exact
+ * arrow pattern keeps.  Returns NULL when memory runs out. */
+static unsigned char *block_table(int N, int n_text, int w, int bm, int bn, int *n_kb_out)
+{
+    const int n_qb = (N + bm - 1) / bm, n_kb = (N + bn - 1) / bn;
+    unsigned char *t = (unsigned char *)calloc((size_t)n_qb * n_kb, 1);
+    if (!t) return NULL;
+    for (int i = 0; i < N; ++i)
+        for (int j = 0; j < N; ++j)
+            if (difa_oracle_allowed(ORACLE_ARROW, i, j, n_text, w)) t[(size_t)(i / bm) * n_kb + j / bn] = 1;
+    *n_kb_out = n_kb;
+    return t;
+}
+
 int difa_oracle_threads(void)
 {
 #ifdef _OPENMP
@@ -80,18 +100,20 @@ int difa_oracle_threads(void)
  * out_raw        : optional [B,H,R,D] of `dtype`; written for CACHE heads only (raw copy)
  * probs          : optional [B,H,R,N] fp64 softmax weights (zero where not allowed;
  *                  untouched for CACHE heads)
+ * block_m, block_n : 0, 0 for the exact band; otherwise the block sizes of the block-granular band
  * returns 0, -1 on an invalid argument, -2 when host memory runs out.
  */
-int difa_oracle_joint_attention(const void *q, const void *k, const void *v, const void *cache,
-                                int dtype, int B, int H, int D,
-                                const int32_t *head_plan, const int32_t *window,
-                                int n_text, int n_img, double scale,
-                                const int32_t *rows, int n_rows,
-                                double *out, void *out_raw, double *probs)
+int difa_oracle_joint_attention_blocks(const void *q, const void *k, const void *v, const void *cache,
+                                       int dtype, int B, int H, int D,
+                                       const int32_t *head_plan, const int32_t *window,
+                                       int n_text, int n_img, double scale,
+                                       const int32_t *rows, int n_rows, int block_m, int block_n,
+                                       double *out, void *out_raw, double *probs)
 {
     const int N = n_text + n_img;
     if (!q || !k || !v || !out || !head_plan || B <= 0 || H <= 0 || D <= 0 || N <= 0) return -1;
     if (n_text < 0 || n_img < 0) return -1;
+    if (block_m < 0 || block_n < 0 || (block_m == 0) != (block_n == 0)) return -1;
     if (dtype != ORACLE_BF16 && dtype != ORACLE_F32) return -1;
     const int R = rows ? n_rows : N;
     for (int h = 0; h < H; ++h) {
@@ -125,11 +147,20 @@ int difa_oracle_joint_attention(const void *q, const void *k, const void *v, con
                 continue;
             }
             const int w = (mode == ORACLE_ARROW) ? window[h] : 0;
+            /* block-granular band: which (query block, key block) pairs this head keeps */
+            unsigned char *blocks = NULL;
+            int n_kb = 0;
+            if (mode == ORACLE_ARROW && block_m > 0) {
+                blocks = block_table(N, n_text, w, block_m, block_n, &n_kb);
+                if (!blocks) return -2;
+            }
+#define KEPT(i, j) (blocks ? blocks[(size_t)((i) / block_m) * n_kb + (j) / block_n] \
+                           : difa_oracle_allowed(mode, (i), (j), n_text, w))
 
             /* this head's keys and values, widened once (exact) */
             double *kd = (double *)malloc((size_t)N * D * sizeof(double));
             double *vd = (double *)malloc((size_t)N * D * sizeof(double));
-            if (!kd || !vd) { free(kd); free(vd); return -2; }
+            if (!kd || !vd) { free(kd); free(vd); free(blocks); return -2; }
             for (size_t e = 0; e < (size_t)N * D; ++e) {
                 kd[e] = widen(k, dtype, head_off + e);
                 vd[e] = widen(v, dtype, head_off + e);
@@ -148,7 +179,7 @@ int difa_oracle_joint_attention(const void *q, const void *k, const void *v, con
                     /* scores of the allowed keys and their maximum */
                     double m = -INFINITY;
                     for (int j = 0; j < N; ++j) {
-                        if (!difa_oracle_allowed(mode, i, j, n_text, w)) continue;
+                        if (!KEPT(i, j)) continue;
                         double s = 0.0;
                         for (int d = 0; d < D; ++d)
                             s += qi[d] * kd[(size_t)j * D + d];
@@ -159,7 +190,7 @@ int difa_oracle_joint_attention(const void *q, const void *k, const void *v, con
                     /* weights: exp(s - m) on allowed pairs, exactly 0 elsewhere */
                     double l = 0.0;
                     for (int j = 0; j < N; ++j) {
-                        if (difa_oracle_allowed(mode, i, j, n_text, w)) {
+                        if (KEPT(i, j)) {
                             p[j] = exp(p[j] - m);
                             l += p[j];
                         } else {
@@ -184,7 +215,21 @@ int difa_oracle_joint_attention(const void *q, const void *k, const void *v, con
             }
             free(kd);
             free(vd);
+            free(blocks);
+#undef KEPT
         }
     }
     return 0;
+}
+
+/* The exact band (Sec. 3.1). */
+int difa_oracle_joint_attention(const void *q, const void *k, const void *v, const void *cache,
+                                int dtype, int B, int H, int D,
+                                const int32_t *head_plan, const int32_t *window,
+                                int n_text, int n_img, double scale,
+                                const int32_t *rows, int n_rows,
+                                double *out, void *out_raw, double *probs)
+{
+    return difa_oracle_joint_attention_blocks(q, k, v, cache, dtype, B, H, D, head_plan, window, n_text, n_img,
+                                              scale, rows, n_rows, 0, 0, out, out_raw, probs);
 }

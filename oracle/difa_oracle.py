@@ -30,6 +30,13 @@ def lib():
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_double,
             ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.difa_oracle_joint_attention_blocks.restype = ctypes.c_int
+        L.difa_oracle_joint_attention_blocks.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_double,
+            ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         L.difa_oracle_allowed.restype = ctypes.c_int
         L.difa_oracle_allowed.argtypes = [ctypes.c_int] * 5
         L.difa_oracle_threads.restype = ctypes.c_int
@@ -47,11 +54,13 @@ def allowed(mode: int, i: int, j: int, n_text: int, w: int) -> bool:
 
 
 def joint_attention(q, k, v, cache, head_plan, window, n_text, n_img, scale=None,
-                    rows=None, want_probs=False):
+                    rows=None, want_probs=False, block=None):
     """Evaluate the operator on CPU tensors q, k, v (and cache) of shape [B,H,N,D].
 
     dtype bf16 or fp32; the values are widened exactly to fp64.
     rows: optional 1-D integer sequence of query rows (default: all).
+    block: None for the exact band, or (bm, bn) for the block-granular band of Sec. 3.3 / Fig. 4
+    (an ARROW head keeps every pair of a bm x bn block that holds a pair of the exact pattern).
     Returns (out_f64 [B,H,R,D], out_raw [B,H,R,D] of the input dtype -- meaningful
     on CACHE heads only, elsewhere zero --, probs [B,H,R,N] or None).
     """
@@ -76,10 +85,11 @@ def joint_attention(q, k, v, cache, head_plan, window, n_text, n_img, scale=None
     out = np.zeros((B, H, R, D), dtype=np.float64)
     out_raw = torch.zeros((B, H, R, D), dtype=q.dtype)
     probs = np.zeros((B, H, R, N), dtype=np.float64) if want_probs else None
-    rc = lib().difa_oracle_joint_attention(
+    bm, bn = (0, 0) if block is None else (int(block[0]), int(block[1]))
+    rc = lib().difa_oracle_joint_attention_blocks(
         q.data_ptr(), k.data_ptr(), v.data_ptr(), cache.data_ptr() if cache is not None else None,
         _DT[q.dtype], B, H, D, hp.ctypes.data, win.ctypes.data, int(n_text), int(n_img),
-        float(scale), rows_ptr, R, out.ctypes.data, out_raw.data_ptr(),
+        float(scale), rows_ptr, R, bm, bn, out.ctypes.data, out_raw.data_ptr(),
         probs.ctypes.data if probs is not None else None)
     if rc != 0:
         raise ValueError(f"difa_oracle_joint_attention: invalid argument (rc={rc})")

@@ -15,6 +15,7 @@ DIFA_OK, DIFA_ERR_INVALID_ARG, DIFA_ERR_UNSUPPORTED, DIFA_ERR_ALLOC, DIFA_ERR_HI
 DIFA_HEAD_FULL, DIFA_HEAD_ARROW, DIFA_HEAD_CACHE = 0, 1, 2
 DIFA_DTYPE_BF16, DIFA_DTYPE_F32 = 0, 1
 DIFA_LAYOUT_BHND, DIFA_LAYOUT_BNHD = 0, 1
+DIFA_FLAG_BLOCK_BAND = 1
 
 
 class difa_plan_desc_t(ctypes.Structure):
@@ -58,7 +59,7 @@ def _load():
     L.difa_tile_shape.restype = i32
     L.difa_tile_shape.argtypes = [i32, i32, i32p, i32p]
     L.difa_worklist_build.restype = ctypes.c_int
-    L.difa_worklist_build.argtypes = [i32, i32, vp, vp, i32, i32, i32, i32, i32, vp, i32, i32p, vp, i32p]
+    L.difa_worklist_build.argtypes = [i32, i32, vp, vp, i32, i32, i32, i32, i32, ctypes.c_uint32, vp, i32, i32p, vp, i32p]
     L.difa_schedule_build.restype = ctypes.c_int
     L.difa_schedule_build.argtypes = [vp, i32, i32, i32, vp, i32, vp, i32p, vp, i32, i32p, i32p]
     L.difa_plan_timing_enable.restype = ctypes.c_int
@@ -97,19 +98,19 @@ def _i32(a):
     return None if a is None else np.ascontiguousarray(np.asarray(a, dtype=np.int32))
 
 
-def difa_worklist_build(batch, heads, head_plan, window, n_text, n_img, bm, bn, n_xcd=1):
+def difa_worklist_build(batch, heads, head_plan, window, n_text, n_img, bm, bn, n_xcd=1, flags=0):
     """Returns (status, items as a numpy structured array, CACHE-head indices)."""
     hp, win = _i32(head_plan), _i32(window)
     n_items, n_copy = ctypes.c_int32(0), ctypes.c_int32(0)
     copy_heads = np.zeros(max(int(heads), 1), dtype=np.int32)
     st = lib.difa_worklist_build(batch, heads, hp.ctypes.data if hp is not None else None,
                                  win.ctypes.data if win is not None else None, n_text, n_img, bm, bn, n_xcd,
-                                 None, 0, ctypes.byref(n_items), None, ctypes.byref(n_copy))
+                                 flags, None, 0, ctypes.byref(n_items), None, ctypes.byref(n_copy))
     if st != DIFA_OK:
         return st, None, None
     items = (difa_work_item_t * max(n_items.value, 1))()
     st = lib.difa_worklist_build(batch, heads, hp.ctypes.data, win.ctypes.data if win is not None else None,
-                                 n_text, n_img, bm, bn, n_xcd, ctypes.cast(items, ctypes.c_void_p), n_items.value,
+                                 n_text, n_img, bm, bn, n_xcd, flags, ctypes.cast(items, ctypes.c_void_p), n_items.value,
                                  ctypes.byref(n_items), copy_heads.ctypes.data, ctypes.byref(n_copy))
     arr = np.frombuffer(items, dtype=np.dtype([(n, np.int32) for n, _ in difa_work_item_t._fields_]),
                         count=n_items.value).copy()

@@ -153,8 +153,9 @@ extern "C" const char* difa_last_error(const difa_plan_t* plan) {
 extern "C" difa_status_t difa_plan_create(const difa_plan_desc_t* desc, difa_plan_t** plan_out) {
     if (plan_out) *plan_out = nullptr;
     if (!desc || !plan_out) return fail(nullptr, DIFA_ERR_INVALID_ARG, "desc and plan_out must not be NULL");
-    if (desc->batch < 1 || desc->heads < 1 || desc->max_tokens < 1 || desc->flags != 0 || desc->device < 0)
-        return fail(nullptr, DIFA_ERR_INVALID_ARG, "batch, heads, max_tokens must be >= 1, device >= 0, flags 0");
+    if (desc->batch < 1 || desc->heads < 1 || desc->max_tokens < 1 ||
+        (desc->flags & ~(uint32_t)DIFA_FLAG_BLOCK_BAND) != 0 || desc->device < 0)
+        return fail(nullptr, DIFA_ERR_INVALID_ARG, "batch, heads, max_tokens must be >= 1, device >= 0, no unknown flag bits");
     if (!(desc->softmax_scale >= 0.f) || isinf(desc->softmax_scale))
         return fail(nullptr, DIFA_ERR_INVALID_ARG, "softmax_scale must be finite and >= 0 (0 = 1/sqrt(head_dim))");
     if (desc->head_dim != 64 && desc->head_dim != 128)
@@ -325,7 +326,7 @@ extern "C" difa_status_t difa_joint_attention(difa_plan_t* p, const void* q, con
         lru->valid = false;
         int32_t n_items = 0, n_copy = 0, n_segs = 0, n_merges = 0, n_slots = 0;
         char* hb = (char*)lru->h_buf;
-        difa_status_t st = difa_worklist_build(B, H, head_plan, window, n_text, n_img, p->bm, p->bn, 1,
+        difa_status_t st = difa_worklist_build(B, H, head_plan, window, n_text, n_img, p->bm, p->bn, 1, p->desc.flags,
                                                p->recs.data(), p->item_capacity, &n_items, (int32_t*)hb, &n_copy);
         if (st != DIFA_OK) return fail(p, st, "work-list compilation failed");
         size_t used = p->heads_bytes;

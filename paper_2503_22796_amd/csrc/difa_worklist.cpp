@@ -66,11 +66,13 @@ extern "C" int32_t difa_tile_shape(int32_t head_dim, int32_t dtype, int32_t* bm,
 
 extern "C" difa_status_t difa_worklist_build(int32_t batch, int32_t heads, const int32_t* head_plan,
                                              const int32_t* window, int32_t n_text, int32_t n_img,
-                                             int32_t bm, int32_t bn, int32_t n_xcd, difa_work_item_t* items,
+                                             int32_t bm, int32_t bn, int32_t n_xcd, uint32_t flags,
+                                             difa_work_item_t* items,
                                              int32_t capacity, int32_t* n_items_out,
                                              int32_t* copy_heads, int32_t* n_copy_out) {
     if (!head_plan || !n_items_out || batch < 1 || heads < 1 || n_text < 0 || n_img < 0 ||
-        bm < 1 || bn < 1 || n_xcd < 1 || n_xcd > 64 || capacity < 0 || (capacity > 0 && !items))
+        bm < 1 || bn < 1 || n_xcd < 1 || n_xcd > 64 || capacity < 0 || (capacity > 0 && !items) ||
+        (flags & ~(uint32_t)DIFA_FLAG_BLOCK_BAND) != 0)
         return DIFA_ERR_INVALID_ARG;
     const int64_t n64 = (int64_t)n_text + (int64_t)n_img;
     if (n64 < 1 || n64 > (int64_t)1 << 30) return DIFA_ERR_INVALID_ARG;
@@ -125,10 +127,14 @@ extern "C" difa_status_t difa_worklist_build(int32_t batch, int32_t heads, const
                         r.kv1_end = std::max(r.kv1_begin, hi / bn + 1);
                     }
                 }
+                // Block-granular band (Sec. 3.3, Fig. 4): every visited block is dense, so the record is
+                // masked like a full head's: on the sequence tail only.
+                const int wm = (flags & DIFA_FLAG_BLOCK_BAND) ? -1 : w;
+                r.window = wm;
                 int b0, e0;
-                mask_free_run(g, w, i0, i1, 0, r.kv0_end, true, &b0, &e0);
+                mask_free_run(g, wm, i0, i1, 0, r.kv0_end, true, &b0, &e0);
                 r.nm0_end = e0;
-                mask_free_run(g, w, i0, i1, r.kv1_begin, r.kv1_end, false, &r.nm1_begin, &r.nm1_end);
+                mask_free_run(g, wm, i0, i1, r.kv1_begin, r.kv1_end, false, &r.nm1_begin, &r.nm1_end);
                 r.n_tiles = r.kv0_end + (r.kv1_end - r.kv1_begin);
                 recs.push_back(r);
                 span.cost += r.n_tiles;

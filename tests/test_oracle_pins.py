@@ -351,3 +351,83 @@ def test_generator_is_seeded_and_diagonal_local():
     b = W.make_qkv(small)
     assert all(torch.equal(x, y) for x, y in zip(a, b))
     assert not torch.equal(a[0], W.make_qkv(small, step=1)[0])
+
+
+# --------------------------------------------------------------------------- block-granular band
+def block_rule(n_text, N, w, bm, bn):
+    """Sec. 3.3 / Fig. 4 restated with explicit loops: a block is kept whole iff it holds a kept pair."""
+    kept = [[False] * N for _ in range(N)]
+    for a in range(0, N, bm):
+        for b in range(0, N, bn):
+            hit = any((i < n_text) or (j < n_text) or abs(i - j) <= w
+                      for i in range(a, min(a + bm, N)) for j in range(b, min(b + bn, N)))
+            if hit:
+                for i in range(a, min(a + bm, N)):
+                    for j in range(b, min(b + bn, N)):
+                        kept[i][j] = True
+    return kept
+
+
+def brute_force_masked(q, k, v, kept, scale):
+    N, D = len(q), len(q[0])
+    out = [[0.0] * D for _ in range(N)]
+    for i in range(N):
+        keys = [j for j in range(N) if kept[i][j]]
+        scores = [scale * sum(q[i][d] * k[j][d] for d in range(D)) for j in keys]
+        top = max(scores)
+        e = [math.exp(s - top) for s in scores]
+        z = sum(e)
+        for jj, j in enumerate(keys):
+            for d in range(D):
+                out[i][d] += e[jj] / z * v[j][d]
+    return torch.tensor(out, dtype=torch.float64)
+
+
+@pytest.mark.parametrize("n_text,n_img,w,bm,bn", [(0, 16, 1, 4, 4), (3, 21, 2, 8, 4), (5, 14, 0, 4, 8),
+                                                   (1, 30, 6, 16, 4), (7, 9, 3, 5, 3)])
+def test_block_band_matches_brute_force(n_text, n_img, w, bm, bn):
+    # catches: block index from the wrong axis, blocks anchored at n_text instead of 0, a dropped ragged block
+    N, D = n_text + n_img, 4
+    q, k, v = (rand((1, 1, N, D), 300 + s + N) for s in range(3))
+    got, _, probs = O.joint_attention(q, k, v, None, [ARROW], [w], n_text, n_img, scale=0.7, block=(bm, bn),
+                                      want_probs=True)
+    kept = block_rule(n_text, N, w, bm, bn)
+    ref = brute_force_masked(q[0, 0].tolist(), k[0, 0].tolist(), v[0, 0].tolist(), kept, 0.7)
+    assert (got[0, 0] - ref).abs().max() < 1e-12
+    assert torch.equal(probs[0, 0] > 0, torch.tensor(kept))
+
+
+def test_block_band_pair_counts_match_hand_counts():
+    for line in open(os.path.join(GOLDEN, "block_band_pair_counts.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        n_text, n_img, w, bm, bn, pairs = (int(x) for x in line.split())
+        N = n_text + n_img
+        q, k, v = (rand((1, 1, N, 2), 400 + s) for s in range(3))
+        _, _, probs = O.joint_attention(q, k, v, None, [ARROW], [w], n_text, n_img, block=(bm, bn), want_probs=True)
+        assert int((probs[0, 0] > 0).sum()) == pairs, line
+
+
+def test_block_band_with_unit_blocks_is_the_exact_band_and_is_a_superset_otherwise():
+    n_text, n_img, w = 6, 40, 5
+    N = n_text + n_img
+    q, k, v = (rand((1, 2, N, 8), 500 + s) for s in range(3))
+    exact, _, p_exact = O.joint_attention(q, k, v, None, [ARROW, FULL], [w, 0], n_text, n_img, want_probs=True)
+    unit, _, _ = O.joint_attention(q, k, v, None, [ARROW, FULL], [w, 0], n_text, n_img, block=(1, 1))
+    assert torch.equal(exact, unit)
+    blk, _, p_blk = O.joint_attention(q, k, v, None, [ARROW, FULL], [w, 0], n_text, n_img, block=(8, 4),
+                                      want_probs=True)
+    assert bool(((p_exact[0, 0] > 0) <= (p_blk[0, 0] > 0)).all())       # every exact pair is still kept
+    assert int((p_blk[0, 0] > 0).sum()) > int((p_exact[0, 0] > 0).sum())
+    assert torch.equal(blk[:, 1], exact[:, 1])                           # FULL heads are untouched
+    assert (p_blk.sum(-1) - 1).abs().max() < 1e-12
+
+
+def test_block_band_covering_window_equals_full():
+    n_text, n_img = 4, 28
+    q, k, v = (rand((1, 2, n_text + n_img, 8), 600 + s) for s in range(3))
+    out, _, _ = O.joint_attention(q, k, v, None, [ARROW, FULL], [n_img - 1, 0], n_text, n_img, block=(8, 8))
+    q2, k2, v2 = q.clone(), k.clone(), v.clone()
+    q2[:, 1], k2[:, 1], v2[:, 1] = q[:, 0], k[:, 0], v[:, 0]
+    full, _, _ = O.joint_attention(q2, k2, v2, None, [ARROW, FULL], [n_img - 1, 0], n_text, n_img, block=(8, 8))
+    assert torch.equal(full[:, 0], full[:, 1])
