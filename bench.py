@@ -31,13 +31,13 @@ def make_workload(name):
     raise SystemExit(f"unknown workload {name}")
 
 
-def cpu_baseline(wl, q, k, v, cache, every):
+def cpu_baseline(wl, q, k, v, cache, every, block=None):
     """The oracle as it stands, timed on this host's cores, on every `every`-th query row."""
     from oracle import difa_oracle as O
     from paper_2503_22796_amd.accounting import allowed_pairs
     rows = list(range(0, wl.N, every))
     t0 = time.perf_counter()
-    O.joint_attention(q, k, v, cache, wl.head_plan, wl.window, wl.n_text, wl.n_img, rows=rows)
+    O.joint_attention(q, k, v, cache, wl.head_plan, wl.window, wl.n_text, wl.n_img, rows=rows, block=block)
     dt = time.perf_counter() - t0
     # FLOPs of exactly the sampled rows (band length depends on the row)
     flops = 0
@@ -130,6 +130,8 @@ def main():
     ap.add_argument("--workload", default="flux_2k_mixed")
     ap.add_argument("--cpu-every", type=int, default=1, help="oracle baseline on every n-th row; 0 = skip")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--block-band", action="store_true",
+                    help="arrow heads use the block-granular band of the paper's kernel (Sec. 3.3) instead of the exact one")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on one GPU only (heads would be sharded across GPUs, "
@@ -150,8 +152,10 @@ def main():
     cache0 = W.make_cache(wl)
     qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)
     bufs = [cache0.to(dev), torch.empty_like(qd)]
-    plan = B.difa_plan_create(wl.B, wl.H, wl.D, max_tokens=wl.N)
-    fl = plan_flops(wl.head_plan, wl.window, wl.n_text, wl.n_img, wl.D, wl.B)
+    plan = B.difa_plan_create(wl.B, wl.H, wl.D, max_tokens=wl.N,
+                              flags=B.DIFA_FLAG_BLOCK_BAND if args.block_band else 0)
+    block = B.difa_tile_shape(wl.D) if args.block_band else None
+    fl = plan_flops(wl.head_plan, wl.window, wl.n_text, wl.n_img, wl.D, wl.B, block=block)
     by = plan_bytes(wl.head_plan, wl.n_text, wl.n_img, wl.D, 2, wl.B)
 
     def step(i):
@@ -205,7 +209,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall_ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": wl.name, "batch": wl.B, "heads": wl.H, "head_dim": wl.D,
+        "config": {"workload": wl.name + ("_block_band" if args.block_band else ""), "batch": wl.B, "heads": wl.H, "head_dim": wl.D,
                    "n_text": wl.n_text, "n_img": wl.n_img,
                    "plan": {"full": int((wl.head_plan == 0).sum()),
                             "arrow": sorted(int(w) for w in wl.window[wl.head_plan == 1]),
@@ -224,7 +228,7 @@ def main():
     B.difa_plan_destroy(plan)
     if not args.no_cpu and args.cpu_every > 0:
         has_cache = bool((wl.head_plan == 2).any())
-        out["cpu_baseline"] = cpu_baseline(wl, q, k, v, cache0 if has_cache else None, args.cpu_every)
+        out["cpu_baseline"] = cpu_baseline(wl, q, k, v, cache0 if has_cache else None, args.cpu_every, block=block)
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out))

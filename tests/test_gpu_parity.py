@@ -245,3 +245,47 @@ def test_kernel_timing_hook():
         assert B.difa_plan_timing_read(plan)[2] == 0
     finally:
         B.difa_plan_destroy(plan)
+
+
+# ----------------------------------------------------------------------------- block-granular band
+def run_block_case(wl, dtype=torch.bfloat16, rows=None):
+    from paper_2503_22796_amd import binding as B
+    bm, bn = B.difa_tile_shape(wl.D, B.DIFA_DTYPE_BF16 if dtype == torch.bfloat16 else B.DIFA_DTYPE_F32)
+    q, k, v = W.make_qkv(wl, dtype=dtype)
+    cache = W.make_cache(wl, dtype=dtype) if (wl.head_plan == CACHE).any() else None
+    out = gpu_joint_attention(q, k, v, cache, wl.head_plan, wl.window, wl.n_text, wl.n_img,
+                              flags=B.DIFA_FLAG_BLOCK_BAND)
+    tol = TOL_BF16 if dtype == torch.bfloat16 else TOL_F32
+    err = check_against_oracle(out, q, k, v, cache, wl.head_plan, wl.window, wl.n_text, wl.n_img, rows=rows,
+                               tol=tol, block=(bm, bn))
+    print(f"{wl.name} (block band {bm}x{bn}): dtype={dtype} max_abs_err={err:.3e}", flush=True)
+    return out, q, k, v
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("n_text,n_img,wins", [
+    (0, 700, [0, 1, 70]),
+    (64, 1024, [63, 64, 300]),
+    (333, 1000, [7, 130, 998]),
+])
+def test_block_band_edge_shapes(D, n_text, n_img, wins):
+    wl = small_workload(2, 4, D, n_text, n_img, [FULL, ARROW, ARROW, ARROW], [0] + wins, seed=200 + n_img)
+    run_block_case(wl)
+
+
+def test_block_band_flux_1k_all_rows_and_it_differs_from_the_exact_band():
+    wl = W.flux_1k()
+    out, q, k, v = run_block_case(wl)
+    exact = gpu_joint_attention(q, k, v, W.make_cache(wl), wl.head_plan, wl.window, wl.n_text, wl.n_img)
+    arrow = [h for h in range(wl.H) if wl.head_plan[h] == ARROW and wl.window[h] < wl.n_img - 1]
+    assert any(not torch.equal(out[:, h], exact[:, h]) for h in arrow)      # the flag is not a no-op
+    others = [h for h in range(wl.H) if wl.head_plan[h] == FULL]
+    # full heads compute the same thing in both runs (their records may be cut at other places, so the
+    # rounding order may differ)
+    assert all(float((out[:, h].float() - exact[:, h].float()).abs().max()) <= TOL_BF16 for h in others)
+
+
+def test_block_band_flux_2k_mixed_sampled_rows():
+    wl = W.flux_2k_mixed()
+    rows = boundary_rows(wl.n_text, wl.n_img, wl.window[wl.head_plan == ARROW], extra=64, seed=14)
+    run_block_case(wl, rows=rows)

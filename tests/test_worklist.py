@@ -217,3 +217,27 @@ def test_schedule_rejects_bad_arguments():
     assert B.difa_schedule_build(items, 0, 1)[0] == B.DIFA_ERR_INVALID_ARG
     st, segs, wg_begin, merges, n_slots = B.difa_schedule_build(items[:0], 8, 8)
     assert st == B.DIFA_OK and len(segs) == 0 and n_slots == 0 and (wg_begin == 0).all()
+
+
+# ----------------------------------------------------------------------------- block-granular band
+@pytest.mark.parametrize("n_text,n_img,bm,bn,heads", CASES)
+def test_block_band_records_visit_the_same_tiles_and_mask_only_the_tail(n_text, n_img, bm, bn, heads):
+    N = n_text + n_img
+    hp, win = [m for m, _ in heads], [w for _, w in heads]
+    H = len(heads)
+    st, exact, _ = B.difa_worklist_build(1, H, hp, win, n_text, n_img, bm, bn, 1)
+    st2, block, _ = B.difa_worklist_build(1, H, hp, win, n_text, n_img, bm, bn, 1, flags=B.DIFA_FLAG_BLOCK_BAND)
+    assert st == B.DIFA_OK and st2 == B.DIFA_OK and len(exact) == len(block)
+    ex = {(int(r["bh"]), int(r["q_tile"])): r for r in exact}
+    n_kv = (N + bn - 1) // bn
+    for r in block:
+        e = ex[(int(r["bh"]), int(r["q_tile"]))]
+        for f in ("kv0_end", "kv1_begin", "kv1_end", "n_tiles"):
+            assert r[f] == e[f]                      # a block is visited iff it holds a kept pair: unchanged
+        assert r["window"] == -1                     # no band edge is masked inside a tile
+        visited = set(range(0, r["kv0_end"])) | set(range(r["kv1_begin"], r["kv1_end"]))
+        mask_free = set(range(0, min(r["nm0_end"], r["kv0_end"]))) | \
+            set(range(max(r["nm1_begin"], r["kv1_begin"]), min(r["nm1_end"], r["kv1_end"])))
+        ragged_tail = {n_kv - 1} if N % bn else set()
+        assert mask_free == visited - ragged_tail
+    assert B.difa_worklist_build(1, H, hp, win, n_text, n_img, bm, bn, 1, flags=6)[0] == B.DIFA_ERR_INVALID_ARG

@@ -8,7 +8,7 @@ TOL_F32 = 1e-5    # max-abs bar for the fp32 debug path
 
 
 def gpu_joint_attention(q, k, v, cache, head_plan, window, n_text, n_img, scale=0.0, layout="bhnd",
-                        poison=True, stream=None, plan=None, alias_out_to_cache=False):
+                        poison=True, stream=None, plan=None, alias_out_to_cache=False, flags=0):
     """Run difa_joint_attention on cuda:0.  CPU tensors [B,H,N,D] in, CPU tensor [B,H,N,D] out."""
     from paper_2503_22796_amd import binding as B
     dev = torch.device("cuda:0")
@@ -31,7 +31,7 @@ def gpu_joint_attention(q, k, v, cache, head_plan, window, n_text, n_img, scale=
             od.fill_(float("nan"))
     own = plan is None
     if own:
-        plan = B.difa_plan_create(Bn, H, D, dtype=dt, layout=lay, max_tokens=N, softmax_scale=scale)
+        plan = B.difa_plan_create(Bn, H, D, dtype=dt, layout=lay, max_tokens=N, softmax_scale=scale, flags=flags)
     try:
         B.difa_joint_attention(plan, qd, kd, vd, od, cd, head_plan, n_text, n_img, window, stream=stream)
         torch.cuda.synchronize()
@@ -43,11 +43,11 @@ def gpu_joint_attention(q, k, v, cache, head_plan, window, n_text, n_img, scale=
 
 
 def check_against_oracle(out, q, k, v, cache, head_plan, window, n_text, n_img, scale=None, rows=None,
-                         tol=TOL_BF16):
+                         tol=TOL_BF16, block=None):
     """Element-by-element comparison; returns the max abs error over computed heads."""
     from oracle import difa_oracle as O
     ref, ref_raw, _ = O.joint_attention(q, k, v, cache, head_plan, window, n_text, n_img,
-                                        scale=scale, rows=rows)
+                                        scale=scale, rows=rows, block=block)
     got = out if rows is None else out[:, :, list(rows)]
     hp = np.asarray(head_plan)
     worst = 0.0
