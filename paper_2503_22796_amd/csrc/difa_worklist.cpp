@@ -247,6 +247,104 @@ difa_segment_t whole_segment(const difa_work_item_t& r) {
     return s;
 }
 
+// One die's share of the schedule: a segment list per workgroup, slots numbered from 0.
+struct DiePlan {
+    std::vector<std::vector<difa_segment_t>> lists;
+    std::vector<difa_merge_item_t> merges;
+    int n_slots = 0;
+    int64_t makespan = 0;
+};
+
+void finish_record(DiePlan& plan, const difa_work_item_t& r, std::vector<std::pair<int, difa_segment_t>>& pieces) {
+    if (pieces.size() > 1) {
+        difa_merge_item_t m{r.bh, r.q_tile, plan.n_slots, (int32_t)pieces.size()};
+        for (auto& pc : pieces) pc.second.part_slot = plan.n_slots++;
+        plan.merges.push_back(m);
+    }
+    for (auto& pc : pieces) plan.lists[(size_t)pc.first].push_back(pc.second);
+}
+
+// Whole records dealt in order to the least loaded workgroup (neighbouring query tiles of a head run side
+// by side and share its K/V tiles in the die's L2); the records that no longer fit under the target are cut
+// into pieces that fill the workgroups up to it.
+DiePlan deal_and_cut(const std::vector<difa_work_item_t>& q, int per_die, int64_t target, int slot_budget) {
+    DiePlan plan;
+    plan.lists.resize((size_t)per_die);
+    std::vector<int64_t> load((size_t)per_die, 0);
+    auto least = [&]() { return (int)(std::min_element(load.begin(), load.end()) - load.begin()); };
+    std::vector<difa_work_item_t> pool;
+    for (const difa_work_item_t& r : q) {
+        const int w = least();
+        const int64_t c = range_cost(r, 0, r.n_tiles);
+        if (load[(size_t)w] + c <= target) {
+            plan.lists[(size_t)w].push_back(whole_segment(r));
+            load[(size_t)w] += c;
+        } else {
+            pool.push_back(r);
+        }
+    }
+    for (const difa_work_item_t& r : pool) {
+        std::vector<std::pair<int, difa_segment_t>> pieces;
+        int pos = 0;
+        while (pos < r.n_tiles) {
+            const int w = least();
+            const int remaining = r.n_tiles - pos;
+            const int64_t room = (target - load[(size_t)w] - kSegOverhead) / kUnit;   // in key tiles
+            int take = remaining;
+            const bool may_cut = plan.n_slots + (int)pieces.size() + 2 <= slot_budget;
+            if (may_cut && room >= kMinPiece && room < remaining) {
+                take = (int)room;
+                if (remaining - take < kMinPiece) take = remaining;
+            }
+            difa_segment_t s = whole_segment(r);
+            s.pos_begin = pos;
+            s.pos_end = pos + take;
+            pieces.push_back({w, s});
+            load[(size_t)w] += range_cost(r, pos, pos + take);
+            pos += take;
+        }
+        finish_record(plan, r, pieces);
+    }
+    plan.makespan = *std::max_element(load.begin(), load.end());
+    return plan;
+}
+
+// The records laid end to end and handed out in runs of the target cost: workgroup 0 is filled, then
+// workgroup 1, ...; a record that crosses a boundary is cut there.
+DiePlan fill_in_order(const std::vector<difa_work_item_t>& q, int per_die, int64_t target, int slot_budget) {
+    DiePlan plan;
+    plan.lists.resize((size_t)per_die);
+    std::vector<int64_t> load((size_t)per_die, 0);
+    int w = 0;
+    for (const difa_work_item_t& r : q) {
+        std::vector<std::pair<int, difa_segment_t>> pieces;
+        int pos = 0;
+        while (pos < r.n_tiles) {
+            const int remaining = r.n_tiles - pos;
+            const int64_t room = (target - load[(size_t)w] - kSegOverhead) / kUnit;   // in key tiles
+            int take = remaining;
+            if (w < per_die - 1 && room < remaining) {
+                const bool may_cut = plan.n_slots + (int)pieces.size() + 2 <= slot_budget;
+                if (room < kMinPiece || !may_cut) {
+                    if (load[(size_t)w] > 0) { ++w; continue; }      // this workgroup is full: the next one goes on
+                } else if (remaining - room >= kMinPiece) {
+                    take = (int)room;
+                }                                                     // else: too little would be left over, overfill
+            }
+            difa_segment_t s = whole_segment(r);
+            s.pos_begin = pos;
+            s.pos_end = pos + take;
+            pieces.push_back({w, s});
+            load[(size_t)w] += range_cost(r, pos, pos + take);
+            pos += take;
+            if (w < per_die - 1 && load[(size_t)w] + kSegOverhead + kUnit * kMinPiece > target) ++w;
+        }
+        finish_record(plan, r, pieces);
+    }
+    plan.makespan = *std::max_element(load.begin(), load.end());
+    return plan;
+}
+
 }  // namespace
 
 extern "C" difa_status_t difa_schedule_build(const difa_work_item_t* items, int32_t n_items, int32_t n_wg,
@@ -303,51 +401,29 @@ extern "C" difa_status_t difa_schedule_build(const difa_work_item_t* items, int3
         std::stable_sort(q.begin(), q.end(), [](const difa_work_item_t& a, const difa_work_item_t& b) {
             return a.n_tiles / 16 > b.n_tiles / 16;
         });
-        std::vector<int64_t> load((size_t)per_die, 0);
-        auto least = [&]() { return (int)(std::min_element(load.begin(), load.end()) - load.begin()); };
-        auto wg_of = [&](int w) -> std::vector<difa_segment_t>& { return lists[(size_t)(w * n_xcd + x)]; };
         int64_t die_cost = 0;
         for (const difa_work_item_t& r : q) die_cost += range_cost(r, 0, r.n_tiles);
         // every workgroup is expected to take one extra piece
         const int64_t target = (die_cost + (int64_t)per_die * kSegOverhead + per_die - 1) / per_die;
-        std::vector<difa_work_item_t> pool;
-        for (const difa_work_item_t& r : q) {
-            const int w = least();
-            const int64_t c = range_cost(r, 0, r.n_tiles);
-            if (load[(size_t)w] + c <= target) {
-                wg_of(w).push_back(whole_segment(r));
-                load[(size_t)w] += c;
-            } else {
-                pool.push_back(r);
-            }
+        const int budget = slot_capacity - n_slots - 2 * per_die * (n_xcd - 1 - x);   // this die's share of the slots
+        DiePlan dealt = deal_and_cut(q, per_die, target, budget);
+        // When the records are few and long compared with a workgroup's share (small layers), dealing whole
+        // records leaves the workgroups uneven; filling them one after the other is then the better plan.
+        const int64_t even = die_cost / per_die;
+        if (dealt.makespan * 20 > even * 21) {
+            DiePlan filled = fill_in_order(q, per_die, even + kSegOverhead, budget);
+            if (filled.makespan < dealt.makespan) dealt = std::move(filled);
         }
-        for (const difa_work_item_t& r : pool) {
-            std::vector<std::pair<int, difa_segment_t>> pieces;
-            int pos = 0;
-            while (pos < r.n_tiles) {
-                const int w = least();
-                const int remaining = r.n_tiles - pos;
-                const int64_t room = (target - load[(size_t)w] - kSegOverhead) / kUnit;   // in key tiles
-                int take = remaining;
-                const bool may_cut = n_slots + (int)pieces.size() + 2 <= slot_capacity;
-                if (may_cut && room >= kMinPiece && room < remaining) {
-                    take = (int)room;
-                    if (remaining - take < kMinPiece) take = remaining;
-                }
-                difa_segment_t s = whole_segment(r);
-                s.pos_begin = pos;
-                s.pos_end = pos + take;
-                pieces.push_back({w, s});
-                load[(size_t)w] += range_cost(r, pos, pos + take);
-                pos += take;
+        for (int w = 0; w < per_die; ++w)
+            for (difa_segment_t sg : dealt.lists[(size_t)w]) {
+                if (sg.part_slot >= 0) sg.part_slot += n_slots;
+                lists[(size_t)(w * n_xcd + x)].push_back(sg);
             }
-            if (pieces.size() > 1) {
-                difa_merge_item_t m{r.bh, r.q_tile, n_slots, (int32_t)pieces.size()};
-                for (auto& pc : pieces) pc.second.part_slot = n_slots++;
-                merge_list.push_back(m);
-            }
-            for (auto& pc : pieces) wg_of(pc.first).push_back(pc.second);
+        for (difa_merge_item_t m : dealt.merges) {
+            m.first_slot += n_slots;
+            merge_list.push_back(m);
         }
+        n_slots += dealt.n_slots;
     }
     int64_t n_segs = 0;
     for (const auto& l : lists) n_segs += (int64_t)l.size();
