@@ -209,12 +209,12 @@ extern "C" difa_status_t difa_worklist_build(int32_t batch, int32_t heads, const
 namespace {
 
 // Cost model of a segment, in quarter key-tile iterations (measured on MI355X: a plain iteration takes
-// about 3700 clocks, one whose two blocks go through the element mask up to 5500; the fixed cost of a
-// segment -- first tiles, a slower first iteration, drain, epilogue -- is about four iterations, and
-// a sweep of this constant on the 2K layers put the best balance at ten).
+// about 3700 clocks, one on a masked tile up to 5500 -- per-workgroup fits put it at 0.7-0.9 extra
+// iterations --, and the fixed cost of a segment -- first tiles, a slower first iteration, drain,
+// epilogue -- at about four iterations; a sweep of both constants over the named layers agrees).
 constexpr int kUnit = 4;                  // cost units per key-tile iteration
-constexpr int kMaskedExtra = 2;           // extra units of an iteration on a masked tile
-constexpr int kSegOverhead = 10 * kUnit;  // starting and finishing a segment, the slower first iteration included
+constexpr int kMaskedExtra = 3;           // extra units of an iteration on a masked tile
+constexpr int kSegOverhead = 4 * kUnit;   // starting and finishing a segment
 constexpr int kMinPiece = 8;              // shortest piece (in key tiles) worth cutting off a record
 
 // Masked tiles among positions [p0, p1) of a record's visiting order.
