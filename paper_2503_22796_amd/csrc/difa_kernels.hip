@@ -32,11 +32,16 @@ __device__ __forceinline__ float halves_sum(float x) {
 // ------------------------------------------------------------------------------------------
 // bf16 MFMA attention.
 //
-// One workgroup = 4 wavefronts (one per SIMD) = one 256-row query tile of one (batch, head);
-// wavefront w owns rows 64w..64w+63 as two 32-row blocks.  Key/value tiles of 64 keys go through
-// a 3-stage LDS ring and are visited in the order the host-compiled work record lists them
-// (text tiles, then the band tiles), so a tile with no allowed pair is never loaded
-// (Sec. 3.1 / 3.3: block-sparse band).
+// A workgroup is 4 wavefronts, one per SIMD, and stays resident: it walks the list of segments the
+// host scheduler gave it.  A segment is a 256-row query tile of one (batch, head) together with a
+// run of that record's key/value tiles (the whole run for most records; a few records are cut so
+// that every workgroup ends at the same time, and their pieces leave fp32 partial results that
+// merge_parts_kernel combines).  Wavefront w owns rows 64w..64w+63 as two 32-row blocks.
+// Key/value tiles of 64 keys are written into 4-stage LDS rings by the buffer-load-to-LDS DMA, K three
+// tiles and V two tiles ahead of their use, in the order the work record lists them (text tiles,
+// then the band tiles), so a tile with no allowed pair is never loaded (Sec. 3.1 / 3.3:
+// block-sparse band).  The first tiles and the Q rows of the next segment are requested before
+// the current segment's epilogue.
 //
 // Why 64 rows per wavefront: LDS delivers 128 B/clk/CU, i.e. one 16-byte-per-lane operand read
 // per MFMA issue slot of the CU.  With 32 rows per wavefront every MFMA needs a fresh K or V
@@ -49,8 +54,11 @@ __device__ __forceinline__ float halves_sum(float x) {
 // B operand of O^T = V^T P^T, so P never goes through LDS.  V stays row-major [key][feature] in
 // LDS and its transposed operand comes from ds_read_b64_tr_b16.
 //
-// Software pipeline inside a wavefront: S^T of tile t+1 (MFMA) is issued in the same basic block
-// as the softmax of tile t (VALU), so the two pipes overlap without a second wavefront.
+// Software pipeline inside a wavefront: a wavefront issues in order, so the loop body is laid
+// out by hand as 16 slots per 32-key half-step, each slot one MFMA (S^T of the next block, or
+// P V of the previous one) followed by the few vector instructions of the softmax of the block
+// in between, an LDS operand read or a DMA request; the vector work runs while the matrix core
+// is busy with the slot's MFMA.
 // ------------------------------------------------------------------------------------------
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
