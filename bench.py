@@ -197,6 +197,12 @@ def main():
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                     "traffic": traffic, "traffic_unit": "bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled on a known copy)",
                     "algorithmic_bytes": by["attention"], "avg_kernel_ms": attn_avg, "flop_per_launch": fl["computed"]}
+        # what the matrix cores sustain on this workload's own operand bits with nothing else to do
+        # (the published peak assumes the full clock; N(0,1) operands run into the power limit)
+        sus, sus_ms = B.difa_probe_mfma_rate(kd, waves_per_simd=1, rounds=100000)
+        roofline["sustained_mfma"] = {"value": sus, "unit": "TFLOP/s", "ms": sus_ms,
+                                      "what": "independent v_mfma_f32_32x32x16_bf16 only, operands = this workload's K"}
+        roofline["frac_of_sustained_mfma"] = achieved / sus if sus > 0 else None
     else:
         gbs = by["cache_copy"] / (copy_avg * 1e-3) * 1e-9 if copy_avg > 0 else 0.0
         roofline = {"bound": "hbm", "kernel": "cache_copy_kernel", "achieved": gbs, "peak": 8000.0,

@@ -200,6 +200,22 @@ difa_status_t difa_plan_timing_enable(difa_plan_t* plan, int32_t enable);
 difa_status_t difa_plan_timing_read(difa_plan_t* plan, double* attn_ms, double* copy_ms,
                                     int64_t* launches, int32_t reset);
 
+/* The rate at which the current device sustains dense bf16 MFMA (v_mfma_f32_32x32x16_bf16, the
+ * instruction both contractions of the operator use) on the caller's operand data: a kernel of
+ * nothing but independent MFMAs on every compute unit, timed with HIP events on `stream`.  The
+ * published peak assumes the full clock; for how long a GPU holds it depends on the operand bits
+ * (it is power-limited on N(0,1) data), so a benchmark can report this beside the operator's rate.
+ * Not part of the operator.
+ *   data            device pointer, 16-byte aligned, n_elems bf16 values (>= 8) the operands are taken from.
+ *   waves_per_simd  1 or 2 wavefronts per SIMD.
+ *   rounds          64 MFMAs per wavefront each, in [1, 2^22]; 50 000 rounds take about 50 ms.
+ *   scratch4        device pointer to 4 writable bytes (never written in practice).
+ *   tflops_out, ms_out (ms_out may be NULL)  host.
+ * Synchronises the stream.  Returns DIFA_OK, INVALID_ARG or HIP.
+ */
+difa_status_t difa_probe_mfma_rate(const void* data, int64_t n_elems, int32_t waves_per_simd, int32_t rounds,
+                                   void* scratch4, void* stream, double* tflops_out, double* ms_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -67,6 +67,9 @@ def _load():
     L.difa_plan_timing_read.restype = ctypes.c_int
     L.difa_plan_timing_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
                                         ctypes.POINTER(ctypes.c_int64), i32]
+    L.difa_probe_mfma_rate.restype = ctypes.c_int
+    L.difa_probe_mfma_rate.argtypes = [vp, ctypes.c_int64, i32, i32, vp, vp, ctypes.POINTER(ctypes.c_double),
+                                       ctypes.POINTER(ctypes.c_double)]
     return L
 
 
@@ -191,3 +194,20 @@ def difa_plan_timing_read(plan, reset=True):
     if st != DIFA_OK:
         raise DifaError(st, difa_last_error(plan))
     return a.value, c.value, n.value
+
+
+def difa_probe_mfma_rate(data, waves_per_simd=1, rounds=50000, stream=None):
+    """Sustained dense bf16 MFMA rate on the operand bits of `data` (a bf16 device tensor).
+    Returns (TFLOP/s, milliseconds)."""
+    import torch
+    assert data.is_cuda and data.dtype == torch.bfloat16 and data.is_contiguous()
+    scratch = torch.zeros(1, dtype=torch.float32, device=data.device)
+    t, ms = ctypes.c_double(0), ctypes.c_double(0)
+    s = stream if stream is not None else torch.cuda.current_stream(data.device).cuda_stream
+    with torch.cuda.device(data.device):
+        st = lib.difa_probe_mfma_rate(ctypes.c_void_p(data.data_ptr()), int(data.numel()), int(waves_per_simd),
+                                      int(rounds), ctypes.c_void_p(scratch.data_ptr()), ctypes.c_void_p(s),
+                                      ctypes.byref(t), ctypes.byref(ms))
+    if st != DIFA_OK:
+        raise DifaError(st, "difa_probe_mfma_rate")
+    return t.value, ms.value

@@ -32,21 +32,22 @@ __device__ __forceinline__ float halves_sum(float x) {
 // ------------------------------------------------------------------------------------------
 // bf16 MFMA attention.
 //
-// A workgroup is 4 wavefronts, one per SIMD, and stays resident: it walks the list of segments the
-// host scheduler gave it.  A segment is a 256-row query tile of one (batch, head) together with a
+// A workgroup is 8 / QB wavefronts (QB = 32-row blocks per wavefront; 1 in the shipped build, so eight
+// wavefronts, two per SIMD) and stays resident: it walks the list of segments the host scheduler gave it.  A segment is a 256-row query tile of one (batch, head) together with a
 // run of that record's key/value tiles (the whole run for most records; a few records are cut so
 // that every workgroup ends at the same time, and their pieces leave fp32 partial results that
-// merge_parts_kernel combines).  Wavefront w owns rows 64w..64w+63 as two 32-row blocks.
+// merge_parts_kernel combines).  Wavefront w owns rows 32*QB*w .. 32*QB*(w+1)-1 as QB 32-row blocks.
 // Key/value tiles of 64 keys are written into 4-stage LDS rings by the buffer-load-to-LDS DMA, K three
 // tiles and V two tiles ahead of their use, in the order the work record lists them (text tiles,
 // then the band tiles), so a tile with no allowed pair is never loaded (Sec. 3.1 / 3.3:
 // block-sparse band).  The first tiles and the Q rows of the next segment are requested before
 // the current segment's epilogue.
 //
-// Why 64 rows per wavefront: LDS delivers 128 B/clk/CU, i.e. one 16-byte-per-lane operand read
-// per MFMA issue slot of the CU.  With 32 rows per wavefront every MFMA needs a fresh K or V
-// operand from LDS and the LDS port, not the matrix core, sets the pace; with 64 rows each
-// operand read feeds two MFMAs.
+// Rows per wavefront: with 64 rows (QB = 2) every 16-byte-per-lane LDS operand read feeds two MFMAs,
+// but the whole register file goes to one wavefront per SIMD, and a single wavefront does not overlap
+// its own vector arithmetic with its own MFMAs: measured, the clocks of the two simply add.  With 32
+// rows (QB = 1) a wavefront fits in half the register file, two share a SIMD, and one's softmax runs
+// under the other's MFMAs; LDS (twice the operand reads) is busy about a third of the time.
 //
 // Scores are produced transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: a lane then holds
 // 16 keys of ONE query (column = lane % 32), so the softmax row statistics are per-lane scalars
@@ -55,7 +56,7 @@ __device__ __forceinline__ float halves_sum(float x) {
 // LDS and its transposed operand comes from ds_read_b64_tr_b16.
 //
 // Software pipeline inside a wavefront: a wavefront issues in order, so the loop body is laid
-// out by hand as 16 slots per 32-key half-step, each slot one MFMA (S^T of the next block, or
+// out by hand as 8 * QB slots per 32-key half-step, each slot one MFMA (S^T of the next block, or
 // P V of the previous one) followed by the few vector instructions of the softmax of the block
 // in between, an LDS operand read or a DMA request; the vector work runs while the matrix core
 // is busy with the slot's MFMA.
@@ -95,8 +96,10 @@ struct RowState {
     unsigned span;
 };
 
-template <int D>
-__global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
+template <int D, int QB>
+__global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
+    constexpr int NW = 8 / QB;              // wavefronts per workgroup; each owns 32*QB query rows
+    constexpr int RW = 32 * QB;
     constexpr int KS = D / 16;              // MFMA k-steps of S^T = K Q^T
     constexpr int DB = D / 32;              // 32-row blocks of O^T
     constexpr int CPR = D / 8;              // 16-byte chunks per K/V row
@@ -137,7 +140,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     // view, so the wait for them is explicit (dma_wait) and sits just before the barrier that
     // publishes the tile.
     constexpr int RPI = 64 / CPR;                           // tile rows per load instruction
-    constexpr int NDMA = kBN / RPI / 4;                     // load instructions per wavefront, tensor and tile
+    constexpr int NDMA = kBN / RPI / NW;                     // load instructions per wavefront, tensor and tile
     const unsigned head_bytes = (unsigned)(((int64_t)(N - 1) * a.stride_n + D) * 2);
     uintx4 krsrc, vrsrc;                                    // descriptors of the head whose tiles are being loaded
     const unsigned wave_u = __builtin_amdgcn_readfirstlane(wave);
@@ -172,7 +175,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     // segment's tile p goes to stage (sb + p) % 4) and its query rows in the Q operand registers.
     // Requested ahead of time: for the first segment at once, for every other one by its predecessor,
     // between the end of its own key loop and its epilogue.
-    bf16x8 qf[2][KS];
+    bf16x8 qf[QB][KS];
     auto first_loads = [&](const difa_segment_t& sg, int sb) __attribute__((always_inline)) {
         const int b = sg.bh / a.heads, h = sg.bh - b * a.heads;
         const int64_t base = (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
@@ -195,8 +198,8 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
         }
         const __bf16* qg = (const __bf16*)a.q + base;
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            const int i_r = sg.q_tile * kBM + wave * 64 + 32 * qb + l32;
+        for (int qb = 0; qb < QB; ++qb) {
+            const int i_r = sg.q_tile * kBM + wave * RW + 32 * qb + l32;
             const int i = i_r < N ? i_r : N - 1;            // rows past the end recompute row N-1
             // B operand of S^T = K Q^T: column = query l32, k-slots 8*half..8*half+7 of each 16-wide step
             const __bf16* qrow = qg + (int64_t)i * a.stride_n + 8 * half;
@@ -232,13 +235,13 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
 
     const int b = it.bh / a.heads, h = it.bh - b * a.heads;
     __bf16* __restrict__ og = (__bf16*)a.out + (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
-    const int row0 = it.q_tile * kBM + wave * 64;           // first query row of this wavefront
+    const int row0 = it.q_tile * kBM + wave * RW;           // first query row of this wavefront
 
     // ---- per-lane query rows (two: one per 32-row block) and their allowed key ranges
-    RowState rs[2];
-    int i_raw[2];
+    RowState rs[QB];
+    int i_raw[QB];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
         i_raw[qb] = row0 + 32 * qb + l32;
         const int i = i_raw[qb] < N ? i_raw[qb] : N - 1;
         int lo, hi;
@@ -250,11 +253,11 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
         rs[qb].l = 0.f;
     }
 
-    floatx16 o[DB][2];
+    floatx16 o[DB][QB];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
+        for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) o[db][qb][r] = 0.f;
 
@@ -274,13 +277,13 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     };
 
     // ---- S^T = K Q^T for one 32-key block jb of a tile: s[qb], register r = key 32*jb + 8*(r/4) + 4*half + r%4
-    auto qk_block = [&](int idx, int jb, floatx16 (&s)[2]) {
+    auto qk_block = [&](int idx, int jb, floatx16 (&s)[QB]) {
         const __bf16* kst = &Ksm[((idx + sbase) & 3) * TILE + 32 * jb * D];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const bf16x8 ka = *(const bf16x8*)(kst + koff[ks]);
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
+            for (int qb = 0; qb < QB; ++qb) {
                 if (ks == 0) mfma_s_first(s[qb], ka, qf[qb][ks]);
                 else mfma_s_acc(s[qb], ka, qf[qb][ks]);
             }
@@ -288,12 +291,12 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
         mfma_results_visible();
     };
     // Element mask of one 32-key block whose first key is j0.  The host marks a tile as masked when any
-    // of the workgroup's 256 rows has a forbidden key in it; for the 64 rows of one wavefront most such
+    // of the workgroup's 256 rows has a forbidden key in it; for the rows of one wavefront most such
     // blocks lie entirely inside the band, or are cut by one band edge only.  That is decided here from
     // scalars, so that the common cases cost nothing or one compare per score.
-    const int row_first = it.q_tile * kBM + (int)wave_u * 64;              // this wavefront's rows (uniform)
-    const int row_last = row_first + 63 < N - 1 ? row_first + 63 : N - 1;
-    auto mask_block = [&](int j0, floatx16 (&s)[2]) {
+    const int row_first = it.q_tile * kBM + (int)wave_u * RW;              // this wavefront's rows (uniform)
+    const int row_last = row_first + RW - 1 < N - 1 ? row_first + RW - 1 : N - 1;
+    auto mask_block = [&](int j0, floatx16 (&s)[QB]) {
         const bool plain = j0 >= n_text && row_first >= n_text && j0 + 31 < N && it.window >= 0;
         if (plain) {
             // image rows, image keys, no tail: row i allows keys [i - w, i + w]
@@ -307,7 +310,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
             const float ninf = -INFINITY;
             if (low && !high) {
 #pragma unroll
-                for (int qb = 0; qb < 2; ++qb) {
+                for (int qb = 0; qb < QB; ++qb) {
                     const int edge = rs[qb].lo - j0 - 4 * half;
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
@@ -321,7 +324,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
             }
             if (high && !low) {
 #pragma unroll
-                for (int qb = 0; qb < 2; ++qb) {
+                for (int qb = 0; qb < QB; ++qb) {
                     const int edge = rs[qb].lo + (int)rs[qb].span - j0 - 4 * half;
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
@@ -335,7 +338,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
             }
         }
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
+        for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int j = j0 + 8 * (r >> 2) + 4 * half + (r & 3);
@@ -345,7 +348,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
             }
     };
     // ---- softmax of one 32-key block, cut into 16 pieces of six VALU instructions, one per slot, each
-    // split in two halves that sit behind the slot's two MFMAs (one wavefront per SIMD issues in order:
+    // split in two halves that sit behind the slot's two MFMAs (a wavefront issues in order:
     // whatever is not behind an MFMA delays the next one; the steady state spends nothing on a running
     // maximum).
     //   piece s: scores 2*(s&7), 2*(s&7)+1 of row block s>>3 -> two weights 2^(score*c - reference) as
@@ -359,7 +362,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     // Each piece ends in an empty volatile asm on its results: that keeps it in its slot (otherwise the
     // optimizer sinks the arithmetic to the block that uses it).
     auto pin = [](float& x) { asm volatile("" : "+v"(x)); };
-    auto softmax_a = [&](int s, const floatx16 (&sc)[2], const float (&mneg)[2], float (&x)[2]) __attribute__((always_inline)) {
+    auto softmax_a = [&](int s, const floatx16 (&sc)[QB], const float (&mneg)[QB], float (&x)[2]) __attribute__((always_inline)) {
         const int qb = s >> 3, r = 2 * (s & 7);
         x[0] = __builtin_amdgcn_exp2f(fmaf(sc[qb][r], c, mneg[qb]));
         x[1] = fmaf(sc[qb][r + 1], c, mneg[qb]);
@@ -368,7 +371,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     };
     // (the row-sum update of a pair trails its conversion by one slot: a dot product issued right after
     // the conversion it reads costs a wait state, as does a conversion right after its exponential)
-    auto softmax_b = [&](int s, float (&x)[2], float (&lb)[2], bf16x8 (&pw)[2][2], unsigned& held) __attribute__((always_inline)) {
+    auto softmax_b = [&](int s, float (&x)[2], float (&lb)[QB], bf16x8 (&pw)[QB][2], unsigned& held) __attribute__((always_inline)) {
         const int qb = s >> 3, r = 2 * (s & 7);
         bf16x2 ones;
         ones[0] = (__bf16)1.0f;
@@ -395,10 +398,10 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     // reference; the block's weights and row sums are recomputed, the running sums and O are scaled.
     // The accumulators live in accumulation registers and are scaled in place there; the waits cover
     // MFMA results still in flight.
-    auto renormalise = [&](const floatx16 (&sc)[2], float (&mneg)[2], float (&lb)[2], bf16x8 (&pw)[2][2], bool rescale_o) __attribute__((always_inline)) {
-        float alpha[2];
+    auto renormalise = [&](const floatx16 (&sc)[QB], float (&mneg)[QB], float (&lb)[QB], bf16x8 (&pw)[QB][2], bool rescale_o) __attribute__((always_inline)) {
+        float alpha[QB];
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
+        for (int qb = 0; qb < QB; ++qb) {
             float tmax = -INFINITY;
 #pragma unroll
             for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sc[qb][r]);
@@ -429,7 +432,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb)
+            for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     float e = o[db][qb][r], t;
@@ -455,39 +458,41 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     // ordinary registers, this is where it has to move them over: a vector write needs two wait states
     // before a matrix instruction reads it, and only here are those guaranteed.
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
+    for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[qb][ks]));
     asm volatile("s_nop 1" ::: "memory");
     __syncthreads();
 
     // The pipeline advances by 32-key blocks g = 2*tile + jb.  One half-step for block g is one basic
-    // block of 16 slots; slot s issues
+    // block of 8 * QB slots; slot s issues
     //     MFMA s of S^T of block g+1   | two pieces of the softmax of block g |   MFMA s of P V of block g-1
     // so that consecutive MFMAs never depend on each other and every MFMA has a few VALU
-    // instructions behind it.  LDS operands are fetched three operands (six slots) ahead, across
-    // half-step boundaries.  Two rare side blocks follow and modify registers in place: the rescale
-    // of O by the factors the softmax just produced (after P V of block g-1, before P V of block g)
-    // and the element mask of the scores of block g+1.  K tiles live in a 3-deep ring, V tiles in a
-    // 4-deep ring because P V of a tile's second block runs one iteration after its S^T.  In the
-    // last iteration block g+1 is a reload of the last tile whose scores are never used.
+    // instructions behind it.  LDS operands are fetched three operands ahead, across half-step
+    // boundaries.  Two rare side blocks follow and modify registers in place: the rescale of O by the
+    // factors the softmax just produced (after P V of block g-1, before P V of block g) and the
+    // element mask of the scores of block g+1.  In the last iteration block g+1 is a reload of the
+    // last tile whose scores are never used.
     constexpr int NOP = D / 16;             // LDS operands per MFMA stream per half-step: 8 at D=128, 4 at D=64
-    constexpr int NMF = 2 * NOP;            // MFMAs per stream per half-step
+    constexpr int NMF = QB * NOP;           // MFMAs per stream per half-step
+    constexpr int NSLOT = 8 * QB;           // slots per half-step: one per pair of scores of a lane
     constexpr int AHEAD = 3;                // operands in flight per stream
     static_assert(NOP == 8 || NOP == 4, "slot layout assumes head_dim 128 or 64");
-    floatx16 s0[2], s1[2];                  // scores of the even / odd block in flight
-    bf16x8 pa[2][2], pb[2][2];              // weights of the even / odd block in flight
+    floatx16 s0[QB], s1[QB];                  // scores of the even / odd block in flight
+    bf16x8 pa[QB][2], pb[QB][2];              // weights of the even / odd block in flight
     bf16x8 kq[NOP], vq[NOP];                // LDS operands (entry j = operand j of the stream)
 
-    auto half_step = [&](const floatx16 (&s_cur)[2], floatx16 (&s_nxt)[2], const bf16x8 (&p_prev)[2][2],
-                         bf16x8 (&p_cur)[2][2], const __bf16* kst_nxt, const __bf16* kst_after,
+    auto half_step = [&](const floatx16 (&s_cur)[QB], floatx16 (&s_nxt)[QB], const bf16x8 (&p_prev)[QB][2],
+                         bf16x8 (&p_cur)[QB][2], const __bf16* kst_nxt, const __bf16* kst_after,
                          const __bf16* vst_prev, const __bf16* vst_cur, bool with_pv, bool mask_nxt,
                          int blk_nxt, int dma_tensor, unsigned dma_tb, unsigned dma_dst) __attribute__((always_inline)) {
-        float mneg[2] = {-rs[0].m, -rs[1].m}, lb[2];
+        float mneg[QB], lb[QB];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) mneg[qb] = -rs[qb].m;
         unsigned held = 0;
 #pragma unroll
-        for (int s = 0; s < 16; ++s) {
-            const int j = s >> 1, qb = s & 1, jn = j + AHEAD;    // operand jn is fetched while operand j is used
+        for (int s = 0; s < NSLOT; ++s) {
+            const int j = s / QB, qb = s % QB, jn = j + AHEAD;    // operand jn is fetched while operand j is used
             float x[2];
             if (s < NMF) {
                 if (j == 0) mfma_s_first(s_nxt[qb], kq[j], qf[qb][j]);
@@ -509,7 +514,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
             }
             softmax_b(s, x, lb, p_cur, held);
             // the loads of a later tile are spread over the slots (a burst of them right after the
-            // barrier stalls all four wavefronts on the one memory pipe)
+            // barrier stalls all wavefronts on the one memory pipe)
             if ((s & 3) == 1 && (s >> 2) < NDMA) dma_part(dma_tensor, s >> 2, dma_tb, dma_dst);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -517,12 +522,12 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
             bf16x2 ones;
             ones[0] = (__bf16)1.0f;
             ones[1] = (__bf16)1.0f;
-            lb[1] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, held), ones, lb[1], false);
+            lb[QB - 1] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, held), ones, lb[QB - 1], false);
         }
-        if (__builtin_expect(__builtin_amdgcn_ballot_w64(fmaxf(lb[0], lb[1]) > kTrip) != 0, 0))
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(fmaxf(lb[0], lb[QB - 1]) > kTrip) != 0, 0))
             renormalise(s_cur, mneg, lb, p_cur, with_pv);
-        rs[0].l += lb[0];
-        rs[1].l += lb[1];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) rs[qb].l += lb[qb];
         // block number blk_nxt = 2*position + jb; its first key is only needed on this rare path
         if (__builtin_expect(mask_nxt, 0)) {
             mfma_results_visible();
@@ -536,7 +541,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
 
     // Loop-carried scalars (all uniform over the wavefront), advanced once per iteration instead of
     // being recomputed from the position: ring stages of the tiles in use, mask flags, load target.
-    // With one wavefront per SIMD nothing hides scalar work, so there is as little of it as possible.
+    // A wavefront issues in order and scalar work delays its next MFMA, so there is as little of it as possible.
     const int m0e = (it.nm0_end < it.kv0_end ? it.nm0_end : it.kv0_end) - it.pos_begin;   // idx in [.., m0e) and
     const int m1b = it.kv0_end + (it.nm1_begin > it.kv1_begin ? it.nm1_begin - it.kv1_begin : 0) - it.pos_begin;
     const int m1e = it.kv0_end + ((it.nm1_end < it.kv1_end ? it.nm1_end : it.kv1_end) - it.kv1_begin) - it.pos_begin;
@@ -555,6 +560,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     for (int j = 0; j < AHEAD; ++j) kq[j] = k_operand(kptr(k_cur, 1), j);
     half_step(s0, s1, pb, pa, kptr(k_cur, 1), kptr(k_nxt, 0), vptr(v_cur, 0), vptr(v_cur, 0), false,
               msk_cur, 1, 0, tb_k, k_lds + (unsigned)(k_ld * 2) + wave_lds);
+    if (QB == 1) mfma_results_visible();    // no P V MFMA separated this block's last S^T MFMA from its first reader
     half_step(s1, s0, pa, pb, kptr(k_nxt, 0), kptr(k_nxt, 1), vptr(v_cur, 0), vptr(v_cur, 1), true,
               msk_nxt, 2, 1, tb_v, v_lds + (unsigned)(v_ld * 2) + wave_lds);
     dma_wait_older();
@@ -591,7 +597,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
         for (int i = 0; i < NOP; ++i) {
             if (i + AHEAD < NOP) vq[i + AHEAD] = v_operand(vst, i + AHEAD);
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb)
+            for (int qb = 0; qb < QB; ++qb)
                 o[i >> 1][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vq[i], pb[qb][i & 1], o[i >> 1][qb], 0, 0, 0);
         }
     }
@@ -604,7 +610,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
         // the next segment's loads already in flight, more memory instructions than the 63 the counter
         // can track would stall the wavefront until loads return).
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
+        for (int qb = 0; qb < QB; ++qb) {
             const float l_tot = halves_sum(rs[qb].l);
             const float inv = 1.0f / l_tot;
             __bf16* orow = og + (int64_t)(i_raw[qb] < N ? i_raw[qb] : N - 1) * a.stride_n;
@@ -641,9 +647,9 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
         float* po = a.part_o + (int64_t)it.part_slot * (kBM * D);
         float* pml = a.part_ml + (int64_t)it.part_slot * (kBM * 2);
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
+        for (int qb = 0; qb < QB; ++qb) {
             const float l_tot = halves_sum(rs[qb].l);
-            const int rl = wave * 64 + 32 * qb + l32;        // row inside the query tile
+            const int rl = wave * RW + 32 * qb + l32;        // row inside the query tile
             if (i_raw[qb] < N) {
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
@@ -705,13 +711,21 @@ __global__ __launch_bounds__(256) void merge_parts_kernel(AttnArgs a) {
     }
 }
 
+// 32-row blocks per wavefront (the kernel's QB).  1: eight wavefronts per workgroup, two per SIMD, so that
+// one wavefront's softmax arithmetic runs while the other's MFMA occupies the matrix core; 2: four
+// wavefronts, one per SIMD, each LDS operand read feeding two MFMAs.  Measured on one MI355X, 1 against 2:
+// 16 % fewer clocks per key tile, and at the 1K layers, head_dim 64 and narrow windows 5-19 % less time;
+// at the long 2K layers the time is the same, because there the chip runs at its power limit and
+// lowers its clock by as much as the schedule got tighter.
+constexpr int kRowBlocks = 1;
+
 hipError_t launch_attn_bf16(const AttnArgs& a, int head_dim, int n_wg, int n_merges, hipStream_t stream) {
     if (n_wg <= 0) return hipSuccess;
     if (head_dim == 128) {
-        hipLaunchKernelGGL(attn_bf16_kernel<128>, dim3(n_wg), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((attn_bf16_kernel<128, kRowBlocks>), dim3(n_wg), dim3(512 / kRowBlocks), 0, stream, a);
         if (n_merges > 0) hipLaunchKernelGGL(merge_parts_kernel<128>, dim3(n_merges * kMergeSplit), dim3(256), 0, stream, a);
     } else if (head_dim == 64) {
-        hipLaunchKernelGGL(attn_bf16_kernel<64>, dim3(n_wg), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((attn_bf16_kernel<64, kRowBlocks>), dim3(n_wg), dim3(512 / kRowBlocks), 0, stream, a);
         if (n_merges > 0) hipLaunchKernelGGL(merge_parts_kernel<64>, dim3(n_merges * kMergeSplit), dim3(256), 0, stream, a);
     } else {
         return hipErrorInvalidValue;

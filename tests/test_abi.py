@@ -68,6 +68,19 @@ def test_joint_attention_with_null_plan_is_an_error_not_a_crash():
     assert st == B.DIFA_ERR_INVALID_ARG
 
 
+def test_mfma_rate_probe_rejects_bad_arguments_before_touching_the_gpu():
+    from paper_2503_22796_amd import binding as B
+    t = ctypes.c_double(0)
+    fake = ctypes.c_void_p(4096)
+    call = B.lib.difa_probe_mfma_rate
+    assert call(None, 1024, 1, 10, fake, None, ctypes.byref(t), None) == B.DIFA_ERR_INVALID_ARG      # no data
+    assert call(fake, 1024, 3, 10, fake, None, ctypes.byref(t), None) == B.DIFA_ERR_INVALID_ARG      # 3 wavefronts per SIMD
+    assert call(fake, 1024, 1, 0, fake, None, ctypes.byref(t), None) == B.DIFA_ERR_INVALID_ARG       # no rounds
+    assert call(fake, 4, 1, 10, fake, None, ctypes.byref(t), None) == B.DIFA_ERR_INVALID_ARG         # fewer than 8 values
+    assert call(ctypes.c_void_p(4100), 1024, 1, 10, fake, None, ctypes.byref(t), None) == B.DIFA_ERR_INVALID_ARG   # unaligned
+    assert call(fake, 1024, 1, 10, fake, None, None, None) == B.DIFA_ERR_INVALID_ARG                 # nowhere to put the result
+
+
 def test_product_package_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2503_22796_amd")
     for dirpath, _, files in os.walk(pkg):
