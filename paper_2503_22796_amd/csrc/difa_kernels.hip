@@ -108,8 +108,16 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
     constexpr float kTrip = 0x1p40f;        // a block row sum beyond this sends the wavefront to the renormalising side path
     constexpr float kBump = 16.0f;          // ... where a row's reference moves if its block maximum exceeds it by 2^16
 
-    // K rows: 16-byte chunk c of row r is stored at chunk c ^ (r % CPR)       (conflict-free b128 reads)
-    // V rows: chunk c of row r is stored at chunk c ^ (2 * (r % 4))          (conflict-free transpose reads)
+    // LDS moves 256 bytes per clock over 64 banks of 4 bytes: a b128 read is served 16 lanes at a time
+    // (16 consecutive key rows, one 16-byte chunk each), a transpose read 32 lanes at a time (4 key rows
+    // x 8 pieces of 8 bytes out of one group of 4 chunks).  A 256-byte row (D = 128) covers every bank
+    // once, a 128-byte row (D = 64) half of them, alternating with the row's parity.  The 16-byte chunk c
+    // of row r is therefore stored at chunk c ^ kswz(r) (K) or c ^ vswz(r) (V), chosen so that the
+    // lanes served together land in different banks:
+    //   K: 16 rows x 1 chunk:  D = 128: r % 16;        D = 64: (r / 2) % 8 (rows of one parity share banks)
+    //   V: 4 rows x 4 chunks:  D = 128: 4 * (r % 4);   D = 64: 2 * (r % 4) (the group moves for r % 4 >= 2, the parity does the rest)
+    auto kswz = [](int r) { return CPR == 16 ? (r & 15) : ((r >> 1) & 7); };
+    auto vswz = [](int r) { return CPR == 16 ? 4 * (r & 3) : 2 * (r & 3); };
     __shared__ __attribute__((aligned(16))) __bf16 Ksm[NS * TILE];
     __shared__ __attribute__((aligned(16))) __bf16 Vsm[NS * TILE];
 
@@ -120,14 +128,14 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
     // ---- per-lane LDS offsets (elements, within one stage)
     int koff[KS];                                           // A operand of S^T: row l32, chunk 2*ks+half
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) koff[ks] = l32 * D + 8 * ((2 * ks + half) ^ (l32 & (CPR - 1)));
+    for (int ks = 0; ks < KS; ++ks) koff[ks] = l32 * D + 8 * ((2 * ks + half) ^ kswz(l32));
     int voff[DB];                                           // transpose read: row 4*half + s/4, 4 features
     {
         const int blk = lane >> 4, s16 = lane & 15;
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
             const int chunk = 4 * db + 2 * (blk & 1) + ((s16 & 3) >> 1);
-            voff[db] = (4 * half + (s16 >> 2)) * D + 8 * (chunk ^ (2 * (s16 >> 2))) + 4 * (s16 & 1);
+            voff[db] = (4 * half + (s16 >> 2)) * D + 8 * (chunk ^ vswz(s16 >> 2)) + 4 * (s16 & 1);
         }
     }
 
@@ -148,8 +156,8 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
     for (int u = 0; u < NDMA; ++u) {
         const int r = (wave * NDMA + u) * RPI + lane / CPR, pc = lane % CPR;   // tile row, chunk slot in LDS
-        gk[u] = (unsigned)(r * (int)a.stride_n + 8 * (pc ^ (r & (CPR - 1)))) * 2u;
-        gv[u] = (unsigned)(r * (int)a.stride_n + 8 * (pc ^ (2 * (r & 3)))) * 2u;
+        gk[u] = (unsigned)(r * (int)a.stride_n + 8 * (pc ^ kswz(r))) * 2u;
+        gv[u] = (unsigned)(r * (int)a.stride_n + 8 * (pc ^ vswz(r))) * 2u;
     }
     const unsigned tile_bytes = (unsigned)(kBN * (int)a.stride_n) * 2u;
     const unsigned k_lds = (unsigned)(unsigned long long)(__attribute__((address_space(3))) __bf16*)Ksm;
