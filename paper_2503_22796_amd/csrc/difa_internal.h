@@ -7,7 +7,7 @@
 
 namespace difa {
 
-constexpr int kBM = 256;  // query rows per workgroup (4 wavefronts x 64 rows)
+constexpr int kBM = 256;  // query rows per workgroup (8 wavefronts x 32 rows)
 constexpr int kBN = 64;   // keys per K/V tile
 
 // Arguments common to the attention kernels.  Strides are in elements.
