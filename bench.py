@@ -181,6 +181,20 @@ def main():
     attn_avg = attn_ms / max(launches, 1)
     copy_avg = copy_ms / max(args.steps, 1)
 
+    # calibration helper (Sec. 3.4.1): the per-head influence metric of this layer's two output buffers,
+    # an HBM-bound streaming pass over both
+    rse_out = torch.empty(wl.H, dtype=torch.float32, device=dev)
+    B.difa_head_rse(plan, bufs[0], bufs[1], wl.N, rse_out)
+    B.difa_plan_timing_enable(plan, True)
+    for _ in range(20):
+        B.difa_head_rse(plan, bufs[0], bufs[1], wl.N, rse_out)
+    rse_ms, rse_calls = B.difa_plan_timing_read_head_rse(plan)
+    B.difa_plan_timing_enable(plan, False)
+    rse_bytes = 2 * wl.B * wl.H * wl.N * wl.D * 2
+    rse_avg = rse_ms / max(rse_calls, 1)
+    head_rse = {"avg_kernel_ms": rse_avg, "bytes": rse_bytes, "GBps": rse_bytes / (rse_avg * 1e-3) * 1e-9 if rse_avg > 0 else None,
+                "frac_of_hbm_peak": rse_bytes / (rse_avg * 1e-3) * 1e-9 / 8000.0 if rse_avg > 0 else None}
+
     bm, bn = B.difa_tile_shape(wl.D)
     _, items, _ = B.difa_worklist_build(wl.B, wl.H, wl.head_plan, wl.window, wl.n_text, wl.n_img, bm, bn)
     items = items[items["q_tile"] >= 0] if items is not None else items
@@ -228,6 +242,7 @@ def main():
         "cache_copy": {"avg_kernel_ms": copy_avg, "bytes": by["cache_copy"],
                        "GBps": (by["cache_copy"] / (copy_avg * 1e-3) * 1e-9) if copy_avg > 0 else None},
         "roofline": roofline,
+        "head_rse": head_rse,
         "paper_context": "paper (one NVIDIA A100): ~68% fewer attention FLOPs and up to 1.5x end-to-end at "
                          "FLUX 2K; kernel speed-ups 1.44x/1.96x/3.55x at 25/50/75% sparsity (Table 3)",
     }

@@ -191,6 +191,26 @@ difa_status_t difa_schedule_build(const difa_work_item_t* items, int32_t n_items
                                   int32_t* n_segs_out, difa_merge_item_t* merges, int32_t merge_capacity,
                                   int32_t* n_merges_out, int32_t* n_slots_out);
 
+/* ------------------------------------------------------------------ calibration helper
+ * The influence of a method on each head, as the plan search measures it (Sec. 3.4.1, Eq. 1; Alg. 1:
+ * Influence[h, m] = RSE(O[h], O'[h])):
+ *     rse_out[h] = sum (y_m - y_o)^2 / sum (y_o - mean(y_o))^2,
+ * every sum over all elements head h owns: batch entries, tokens, features.  (The printed Eq. 1 has
+ * the mean of y_o in the numerator as well; the numerator is read as the error against y_o, which
+ * is what makes a perfect method score 0.)
+ *   y_m, y_o   device, 16-byte aligned, laid out like `out` of difa_joint_attention for the plan's batch,
+ *              heads, head_dim, dtype and layout, with n_tokens (<= max_tokens) tokens: the output of the
+ *              method under test and the original output.  Read-only.
+ *   rse_out    device, heads fp32 values, written by this call.  If y_o is constant over a head the
+ *              value is +inf (or NaN when the error is zero too).
+ * Asynchronous on `stream`; allocates nothing (the plan object owns a scratch for partial sums, so
+ * calls on one object from different streams are ordered by an event).  fp32 arithmetic inside one
+ * 16-byte vector, fp64 across vectors: the result is within 1e-5 relative of exact arithmetic.
+ * Returns DIFA_OK, INVALID_ARG or HIP.
+ */
+difa_status_t difa_head_rse(difa_plan_t* plan, const void* y_m, const void* y_o, int32_t n_tokens,
+                            float* rse_out, void* stream);
+
 /* ------------------------------------------------------------------ measurement hooks
  * With timing enabled the library brackets its attention kernel (not the cache copy) with
  * HIP events on the caller's stream; difa_plan_timing_read waits for the last bracket and
@@ -199,6 +219,8 @@ difa_status_t difa_schedule_build(const difa_work_item_t* items, int32_t n_items
 difa_status_t difa_plan_timing_enable(difa_plan_t* plan, int32_t enable);
 difa_status_t difa_plan_timing_read(difa_plan_t* plan, double* attn_ms, double* copy_ms,
                                     int64_t* launches, int32_t reset);
+/* The same for difa_head_rse: accumulated milliseconds of its two kernels and the number of calls. */
+difa_status_t difa_plan_timing_read_head_rse(difa_plan_t* plan, double* rse_ms, int64_t* launches, int32_t reset);
 
 /* The rate at which the current device sustains dense bf16 MFMA (v_mfma_f32_32x32x16_bf16, the
  * instruction both contractions of the operator use) on the caller's operand data: a kernel of

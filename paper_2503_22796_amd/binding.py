@@ -67,6 +67,10 @@ def _load():
     L.difa_plan_timing_read.restype = ctypes.c_int
     L.difa_plan_timing_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
                                         ctypes.POINTER(ctypes.c_int64), i32]
+    L.difa_head_rse.restype = ctypes.c_int
+    L.difa_head_rse.argtypes = [vp, vp, vp, i32, vp, vp]
+    L.difa_plan_timing_read_head_rse.restype = ctypes.c_int
+    L.difa_plan_timing_read_head_rse.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64), i32]
     L.difa_probe_mfma_rate.restype = ctypes.c_int
     L.difa_probe_mfma_rate.argtypes = [vp, ctypes.c_int64, i32, i32, vp, vp, ctypes.POINTER(ctypes.c_double),
                                        ctypes.POINTER(ctypes.c_double)]
@@ -211,3 +215,22 @@ def difa_probe_mfma_rate(data, waves_per_simd=1, rounds=50000, stream=None):
     if st != DIFA_OK:
         raise DifaError(st, "difa_probe_mfma_rate")
     return t.value, ms.value
+
+
+def difa_head_rse(plan, y_m, y_o, n_tokens, rse_out, stream=None):
+    """rse_out[h] = sum (y_m - y_o)^2 / sum (y_o - mean y_o)^2 per head; device tensors, asynchronous."""
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream(y_m.device).cuda_stream
+    st = lib.difa_head_rse(plan, ctypes.c_void_p(y_m.data_ptr()), ctypes.c_void_p(y_o.data_ptr()), int(n_tokens),
+                           ctypes.c_void_p(rse_out.data_ptr()), ctypes.c_void_p(s))
+    if st != DIFA_OK:
+        raise DifaError(st, difa_last_error(plan))
+
+
+def difa_plan_timing_read_head_rse(plan, reset=True):
+    """Returns (milliseconds, calls) of difa_head_rse accumulated while timing was enabled."""
+    a, n = ctypes.c_double(0), ctypes.c_int64(0)
+    st = lib.difa_plan_timing_read_head_rse(plan, ctypes.byref(a), ctypes.byref(n), 1 if reset else 0)
+    if st != DIFA_OK:
+        raise DifaError(st, difa_last_error(plan))
+    return a.value, n.value

@@ -31,7 +31,7 @@ struct Slot {
 
 struct TimingPair {
     hipEvent_t start, stop;
-    int kind;  // 0 attention, 1 copy
+    int kind;  // 0 attention, 1 copy, 2 influence metric
 };
 
 }  // namespace
@@ -48,14 +48,18 @@ struct difa_plan {
     hipEvent_t last_launch = nullptr;   // after the last attention launch (the scratch is shared by all calls)
     hipStream_t last_stream = nullptr;
     bool launched = false;
+    double* rse_part = nullptr;         // device scratch of difa_head_rse: batch * heads * kRseChunks * 3 sums
+    hipEvent_t rse_last = nullptr;      // after the last difa_head_rse launch (same sharing, same ordering)
+    hipStream_t rse_stream = nullptr;
+    bool rse_launched = false;
     std::vector<difa_work_item_t> recs; // host scratch of the work-list compiler
     Slot slots[kSlots];
     uint64_t clock = 0;
     std::string err;
     bool timing = false;
     std::vector<TimingPair> pending, pool;
-    double attn_ms = 0, copy_ms = 0;
-    int64_t launches = 0;
+    double attn_ms = 0, copy_ms = 0, rse_ms = 0;
+    int64_t launches = 0, rse_launches = 0;
 };
 
 namespace {
@@ -123,7 +127,9 @@ hipError_t timing_flush(difa_plan* p) {
         float ms = 0.f;
         if (e == hipSuccess) e = hipEventElapsedTime(&ms, tp.start, tp.stop);
         if (e == hipSuccess) {
-            if (tp.kind == 0) { p->attn_ms += ms; p->launches += 1; } else p->copy_ms += ms;
+            if (tp.kind == 0) { p->attn_ms += ms; p->launches += 1; }
+            else if (tp.kind == 1) p->copy_ms += ms;
+            else { p->rse_ms += ms; p->rse_launches += 1; }
         } else if (first == hipSuccess) {
             first = e;
         }
@@ -228,6 +234,14 @@ extern "C" difa_status_t difa_plan_create(const difa_plan_desc_t* desc, difa_pla
                         hip_msg("allocating work-list buffers", e));
         }
     }
+    e = hipMalloc((void**)&p->rse_part, (size_t)desc->batch * desc->heads * difa::kRseChunks * 3 * sizeof(double));
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&p->rse_last, hipEventDisableTiming);
+    if (e != hipSuccess) {
+        const difa_status_t st = e == hipErrorOutOfMemory ? DIFA_ERR_ALLOC : DIFA_ERR_HIP;
+        const std::string msg = hip_msg("allocating the influence-metric scratch", e);
+        (void)difa_plan_destroy(p);
+        return fail(nullptr, st, msg);
+    }
     *plan_out = p;
     return DIFA_OK;
 }
@@ -246,6 +260,9 @@ extern "C" difa_status_t difa_plan_destroy(difa_plan_t* p) {
     if (p->part_o) (void)hipFree(p->part_o);
     if (p->part_ml) (void)hipFree(p->part_ml);
     if (p->last_launch) (void)hipEventDestroy(p->last_launch);
+    if (p->rse_launched) (void)hipEventSynchronize(p->rse_last);
+    if (p->rse_part) (void)hipFree(p->rse_part);
+    if (p->rse_last) (void)hipEventDestroy(p->rse_last);
     delete p;
     return DIFA_OK;
 }
@@ -267,6 +284,18 @@ extern "C" difa_status_t difa_plan_timing_read(difa_plan_t* p, double* attn_ms, 
     if (copy_ms) *copy_ms = p->copy_ms;
     if (launches) *launches = p->launches;
     if (reset) { p->attn_ms = 0; p->copy_ms = 0; p->launches = 0; }
+    return DIFA_OK;
+}
+
+extern "C" difa_status_t difa_plan_timing_read_head_rse(difa_plan_t* p, double* rse_ms, int64_t* launches, int32_t reset) {
+    if (!p) return DIFA_ERR_INVALID_ARG;
+    DeviceGuard guard;
+    hipError_t e = guard.enter(p->desc.device);
+    if (e == hipSuccess) e = timing_flush(p);
+    if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("reading kernel timing events", e));
+    if (rse_ms) *rse_ms = p->rse_ms;
+    if (launches) *launches = p->rse_launches;
+    if (reset) { p->rse_ms = 0; p->rse_launches = 0; }
     return DIFA_OK;
 }
 
@@ -427,5 +456,42 @@ extern "C" difa_status_t difa_joint_attention(difa_plan_t* p, const void* q, con
     if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("hipEventRecord", e));
     slot->used = true;
     if (p->timing && p->pending.size() > 512) (void)timing_flush(p);
+    return DIFA_OK;
+}
+
+// Influence[h] = RSE(O[h], O'[h]) of Alg. 1 (Sec. 3.4.1, Eq. 1): one streaming pass over both tensors.
+extern "C" difa_status_t difa_head_rse(difa_plan_t* p, const void* y_m, const void* y_o, int32_t n_tokens,
+                                       float* rse_out, void* stream_v) {
+    if (!p) return DIFA_ERR_INVALID_ARG;
+    if (!y_m || !y_o || !rse_out) return fail(p, DIFA_ERR_INVALID_ARG, "y_m, y_o and rse_out must not be NULL");
+    if (n_tokens < 1 || n_tokens > p->desc.max_tokens)
+        return fail(p, DIFA_ERR_INVALID_ARG, "n_tokens must be in [1, max_tokens]");
+    if ((((uintptr_t)y_m | (uintptr_t)y_o) & 15) != 0)
+        return fail(p, DIFA_ERR_INVALID_ARG, "y_m and y_o must be 16-byte aligned");
+    hipStream_t stream = (hipStream_t)stream_v;
+    DeviceGuard guard;
+    hipError_t e = guard.enter(p->desc.device);
+    if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("hipSetDevice", e));
+    const int64_t D = p->desc.head_dim, H = p->desc.heads, N = n_tokens;
+    difa::RseArgs a{};
+    a.y_m = y_m; a.y_o = y_o; a.partial = p->rse_part; a.out = rse_out;
+    if (p->desc.layout == DIFA_LAYOUT_BHND) { a.stride_n = D; a.stride_h = N * D; a.stride_b = H * N * D; }
+    else { a.stride_h = D; a.stride_n = H * D; a.stride_b = N * H * D; }
+    a.batch = p->desc.batch; a.heads = p->desc.heads; a.n_tokens = n_tokens; a.head_dim = p->desc.head_dim;
+    // the partial sums live in one scratch per plan object: order the calls across streams
+    if (p->rse_launched && p->rse_stream != stream) {
+        e = hipStreamWaitEvent(stream, p->rse_last, 0);
+        if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("hipStreamWaitEvent", e));
+    }
+    TimingPair tp{};
+    if (p->timing && (e = timing_begin(p, stream, 2, &tp)) != hipSuccess)
+        return fail(p, DIFA_ERR_HIP, hip_msg("hipEventRecord", e));
+    e = difa::launch_head_rse(a, p->desc.dtype, stream);
+    if (p->timing) { (void)hipEventRecord(tp.stop, stream); p->pending.push_back(tp); }
+    if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("influence-metric launch", e));
+    e = hipEventRecord(p->rse_last, stream);
+    if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("hipEventRecord", e));
+    p->rse_stream = stream;
+    p->rse_launched = true;
     return DIFA_OK;
 }

@@ -35,9 +35,21 @@ struct CopyArgs {
     int32_t batch, n_copy, n_tokens, vec_per_row;  // 16-byte vectors per token row
 };
 
-// Launchers (defined in difa_kernels.hip).  All enqueue on `stream` and return the launch status.
+// Arguments of the influence-metric kernels.  Strides are in elements.
+constexpr int kRseChunks = 64;  // workgroups per (batch, head) of the streaming pass
+struct RseArgs {
+    const void* y_m;
+    const void* y_o;
+    double* partial;  // device scratch: [batch * heads][kRseChunks][3]
+    float* out;       // device: heads values
+    int64_t stride_b, stride_h, stride_n;
+    int32_t batch, heads, n_tokens, head_dim;
+};
+
+// Launchers (defined in difa_kernels.hip and difa_rse.hip).  All enqueue on `stream` and return the launch status.
 hipError_t launch_attn_bf16(const AttnArgs& a, int head_dim, int n_wg, int n_merges, hipStream_t stream);
 hipError_t launch_attn_f32(const AttnArgs& a, int head_dim, int n_items, hipStream_t stream);
 hipError_t launch_cache_copy(const CopyArgs& a, hipStream_t stream);
+hipError_t launch_head_rse(const RseArgs& a, int dtype, hipStream_t stream);
 
 }  // namespace difa
