@@ -114,3 +114,40 @@ def test_rejects_bad_arguments():
         assert B.lib.difa_head_rse(plan, None, None, 8, None, None) == B.DIFA_ERR_INVALID_ARG
     finally:
         B.difa_plan_destroy(plan)
+
+
+def test_influence_matrix_of_one_layer_follows_the_oracle_pipeline():
+    """Alg. 1 up to the solver: every method applied to every head, RSE against full attention."""
+    from paper_2503_22796_amd import binding as B
+    from paper_2503_22796_amd import calibrate as C
+    from paper_2503_22796_amd import workloads as W
+    from oracle import difa_oracle as O
+    from oracle import rse_oracle as R
+    wl = W.Workload("calib", 1, 4, 64, 48, 1024, np.zeros(4, np.int32), np.zeros(4, np.int32), seed=21)
+    q, k, v = W.make_qkv(wl)
+    prev = W.make_cache(wl)
+    methods = [("arrow", 32), ("arrow", 128), ("arrow", 512), ("cache",)]
+    dev = torch.device("cuda:0")
+    plan = B.difa_plan_create(wl.B, wl.H, wl.D, max_tokens=wl.N)
+    try:
+        infl, o_ref = C.influence_matrix(plan, wl.H, q.to(dev), k.to(dev), v.to(dev), wl.n_text, wl.n_img,
+                                         methods, prev_out=prev.to(dev))
+        torch.cuda.synchronize()
+    finally:
+        B.difa_plan_destroy(plan)
+    infl = infl.cpu().double().numpy()
+    assert infl.shape == (wl.H, len(methods))
+    full = np.zeros(wl.H, np.int32)
+    ref_full, _, _ = O.joint_attention(q, k, v, None, full, np.zeros(wl.H, np.int32), wl.n_text, wl.n_img)
+    for j, m in enumerate(methods):
+        if m[0] == "arrow":
+            ref_m, _, _ = O.joint_attention(q, k, v, None, np.full(wl.H, 1, np.int32), np.full(wl.H, m[1], np.int32),
+                                            wl.n_text, wl.n_img)
+        else:
+            ref_m = prev.double()
+        want = R.head_rse(ref_m, ref_full)
+        # the GPU's outputs are rounded to bf16 (2^-9 relative) before the metric sees them: that adds a
+        # noise floor of about 1e-5 to every entry and moves large entries by well under a percent
+        assert np.all(np.abs(infl[:, j] - want) <= 1e-4 + 0.02 * want), (m, infl[:, j], want)
+    # wider windows lose less
+    assert np.all(infl[:, 0] >= infl[:, 1]) and np.all(infl[:, 1] >= infl[:, 2])
