@@ -211,6 +211,24 @@ difa_status_t difa_schedule_build(const difa_work_item_t* items, int32_t n_items
 difa_status_t difa_head_rse(difa_plan_t* plan, const void* y_m, const void* y_o, int32_t n_tokens,
                             float* rse_out, void* stream);
 
+/* Head-wise plan selection for one layer (Sec. 3.4.2, Eq. 2), host only, exact:
+ *     minimise   sum_h ( latency_full + sum_m X[h,m] * (latency[m] - latency_full) )
+ *     subject to sum_h sum_m X[h,m] * influence[h,m] <= delta,
+ *                X[h,m] = 1 only if influence[h,m] <= (c / heads) * delta,
+ *                sum_m X[h,m] <= 1,  X binary.
+ * (The printed objective lists the method latencies only; a head without a method is priced at
+ * latency_full here, without which the minimum would be "choose nothing".)
+ *   influence   host, heads x n_methods, row-major, >= 0: the values difa_head_rse produced per method.
+ *   latency     host, n_methods values >= 0; latency_full >= 0: cost of one head under each method.
+ *   choice_out  host, heads entries: the method index chosen for each head, -1 = full attention.
+ *   total_latency_out, total_influence_out  host, may be NULL.
+ * Among several optimal assignments one is returned.  Returns DIFA_OK, INVALID_ARG (NULL pointers,
+ * negative or NaN values), ALLOC, or UNSUPPORTED when the search frontier outgrows 2^20 entries.
+ */
+difa_status_t difa_plan_solve(const double* influence, const double* latency, double latency_full,
+                              int32_t heads, int32_t n_methods, double delta, double c,
+                              int32_t* choice_out, double* total_latency_out, double* total_influence_out);
+
 /* ------------------------------------------------------------------ measurement hooks
  * With timing enabled the library brackets its attention kernel (not the cache copy) with
  * HIP events on the caller's stream; difa_plan_timing_read waits for the last bracket and

@@ -67,6 +67,9 @@ def _load():
     L.difa_plan_timing_read.restype = ctypes.c_int
     L.difa_plan_timing_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
                                         ctypes.POINTER(ctypes.c_int64), i32]
+    L.difa_plan_solve.restype = ctypes.c_int
+    L.difa_plan_solve.argtypes = [vp, vp, ctypes.c_double, i32, i32, ctypes.c_double, ctypes.c_double, vp,
+                                  ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     L.difa_head_rse.restype = ctypes.c_int
     L.difa_head_rse.argtypes = [vp, vp, vp, i32, vp, vp]
     L.difa_plan_timing_read_head_rse.restype = ctypes.c_int
@@ -234,3 +237,17 @@ def difa_plan_timing_read_head_rse(plan, reset=True):
     if st != DIFA_OK:
         raise DifaError(st, difa_last_error(plan))
     return a.value, n.value
+
+
+def difa_plan_solve(influence, latency, latency_full, delta, c):
+    """Eq. 2 for one layer.  influence [H, M], latency [M] (host).  Returns (status, choice [H] with -1 = full
+    attention, total latency, total influence)."""
+    infl = np.ascontiguousarray(influence, dtype=np.float64)
+    lat = np.ascontiguousarray(latency, dtype=np.float64)
+    H, M = infl.shape
+    assert lat.shape == (M,)
+    choice = np.full(H, -2, dtype=np.int32)
+    tl, ti = ctypes.c_double(0), ctypes.c_double(0)
+    st = lib.difa_plan_solve(infl.ctypes.data, lat.ctypes.data, float(latency_full), H, M, float(delta), float(c),
+                             choice.ctypes.data, ctypes.byref(tl), ctypes.byref(ti))
+    return st, choice, tl.value, ti.value

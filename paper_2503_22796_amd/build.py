@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdifa.so")
-SOURCES = ["difa_api.cpp", "difa_worklist.cpp", "difa_kernels.hip", "difa_rse.hip", "difa_probe.hip"]
+SOURCES = ["difa_api.cpp", "difa_worklist.cpp", "difa_solver.cpp", "difa_kernels.hip", "difa_rse.hip", "difa_probe.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

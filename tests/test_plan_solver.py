@@ -1,0 +1,90 @@
+"""difa_plan_solve (Eq. 2, host code of the library) against the brute-force oracle and a MILP library."""
+import ctypes
+import time
+
+import numpy as np
+import pytest
+
+from oracle import plan_oracle as P
+from test_plan_oracle_pins import hand_cases, milp_optimum, LAT, L_FULL
+
+
+def feasible(infl, lat, l_full, delta, c, choice):
+    infl = np.asarray(infl)
+    H = len(infl)
+    tot_i = 0.0
+    tot_l = 0.0
+    for h, m in enumerate(choice):
+        if m < 0:
+            tot_l += l_full
+            continue
+        assert infl[h][m] <= c / H * delta
+        tot_i += infl[h][m]
+        tot_l += lat[m]
+    assert tot_i <= delta
+    return tot_l, tot_i
+
+
+def test_hand_worked_cases():
+    from paper_2503_22796_amd import binding as B
+    for delta, c, infl, want in hand_cases():
+        st, choice, tl, ti = B.difa_plan_solve(infl, LAT, L_FULL, delta, c)
+        assert st == B.DIFA_OK and tl == want
+        got_l, got_i = feasible(infl, LAT, L_FULL, delta, c, choice)
+        assert got_l == want and abs(got_i - ti) <= 1e-12
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_small_random_instances_against_brute_force(seed):
+    from paper_2503_22796_amd import binding as B
+    g = np.random.Generator(np.random.PCG64(1000 + seed))
+    H, M = int(g.integers(1, 7)), int(g.integers(1, 5))
+    infl = g.uniform(0.0, 1.0, size=(H, M))
+    if seed % 5 == 0:
+        infl = np.round(infl * 4) / 4          # many ties and zeros
+    lat = g.uniform(0.0, 12.0, size=M)         # some methods slower than full attention (10): never chosen
+    delta, c = float(g.uniform(0.0, 2.0)), float(g.uniform(0.5, 4.0))
+    best, assigns = P.solve(infl.tolist(), lat.tolist(), 10.0, delta, c)
+    st, choice, tl, ti = B.difa_plan_solve(infl, lat, 10.0, delta, c)
+    assert st == B.DIFA_OK
+    assert abs(tl - best) <= 1e-9 * max(1.0, best)
+    got_l, _ = feasible(infl, lat.tolist(), 10.0, delta, c, choice)
+    assert abs(got_l - best) <= 1e-9 * max(1.0, best)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_layer_sized_instance_against_a_milp_library(seed):
+    from paper_2503_22796_amd import binding as B
+    g = np.random.Generator(np.random.PCG64(77 + seed))
+    H, M = 24, 6                                # a FLUX layer: arrow at five windows, output caching
+    scale = np.array([0.30, 0.16, 0.08, 0.03, 0.01, 0.5])
+    infl = g.uniform(0.2, 1.8, size=(H, M)) * scale[None, :] * g.uniform(0.2, 3.0, size=(H, 1))
+    lat = np.array([1.0, 1.6, 2.6, 4.4, 7.0, 0.05])
+    delta, c = [0.4, 0.8, 1.5, 3.0][seed], 2.5
+    t0 = time.perf_counter()
+    st, choice, tl, ti = B.difa_plan_solve(infl, lat, 10.0, delta, c)
+    dt = time.perf_counter() - t0
+    assert st == B.DIFA_OK
+    got_l, got_i = feasible(infl, lat.tolist(), 10.0, delta, c, choice)
+    assert abs(got_l - tl) <= 1e-9 and abs(got_i - ti) <= 1e-12
+    want = milp_optimum(infl, lat, 10.0, delta, c)
+    assert abs(tl - want) <= 1e-6, (tl, want)
+    print(f"difa_plan_solve H={H} M={M} delta={delta}: {dt * 1e3:.2f} ms, latency {tl:.2f}, influence {ti:.3f}")
+    assert dt < 5.0
+
+
+def test_limits_and_bad_arguments():
+    from paper_2503_22796_amd import binding as B
+    infl = np.array([[0.2, 0.5], [0.1, 0.4]])
+    st, choice, tl, _ = B.difa_plan_solve(infl, [3.0, 0.0], 10.0, 0.0, 2.0)
+    assert st == B.DIFA_OK and list(choice) == [-1, -1] and tl == 20.0
+    st, choice, tl, _ = B.difa_plan_solve(infl, [3.0, 0.0], 10.0, 1e9, 2.0)
+    assert st == B.DIFA_OK and list(choice) == [1, 1] and tl == 0.0
+    for bad in (dict(delta=-1.0), dict(c=-1.0), dict(latency_full=float("nan"))):
+        kw = dict(latency_full=10.0, delta=1.0, c=1.0)
+        kw.update(bad)
+        st, *_ = B.difa_plan_solve(infl, [3.0, 0.0], kw["latency_full"], kw["delta"], kw["c"])
+        assert st == B.DIFA_ERR_INVALID_ARG
+    st, *_ = B.difa_plan_solve(np.array([[-0.1]]), [1.0], 10.0, 1.0, 1.0)
+    assert st == B.DIFA_ERR_INVALID_ARG
+    assert B.lib.difa_plan_solve(None, None, 1.0, 1, 1, 1.0, 1.0, None, None, None) == B.DIFA_ERR_INVALID_ARG
