@@ -60,25 +60,33 @@ static double widen(const void *base, int dtype, size_t idx)
 
 static size_t elem_size(int dtype) { return dtype == ORACLE_BF16 ? 2 : 4; }
 
-/* Sec. 3.1: which (query i, key j) pairs a head in a given mode attends to. */
+/* Sec. 3.1: which (query i, key j) pairs a head in a given mode attends to.  The text tokens sit in
+ * front of the image tokens (image_first == 0: text is [0, n_text)) or behind them (image_first != 0:
+ * text is [n_img, n_img + n_text)); the paper only says the two are concatenated. */
+int difa_oracle_allowed_order(int mode, int i, int j, int n_text, int n_img, int w, int image_first)
+{
+    const int t0 = image_first ? n_img : 0;     /* first text token */
+    if (mode == ORACLE_FULL) return 1;
+    if (i >= t0 && i < t0 + n_text) return 1;   /* language-to-anything            */
+    if (j >= t0 && j < t0 + n_text) return 1;   /* visual-to-language              */
+    return abs(i - j) <= w;                     /* visual-to-visual: local band    */
+}
+
 int difa_oracle_allowed(int mode, int i, int j, int n_text, int w)
 {
-    if (mode == ORACLE_FULL) return 1;
-    if (i < n_text) return 1;              /* language-to-anything            */
-    if (j < n_text) return 1;              /* visual-to-language              */
-    return abs(i - j) <= w;                /* visual-to-visual: local band    */
+    return difa_oracle_allowed_order(mode, i, j, n_text, 0, w, 0);
 }
 
 /* Sec. 3.3 / Fig. 4: blocks[(i / bm) * n_kb + j / bn] = 1 iff the block holds a pair the exact
  * arrow pattern keeps.  Returns NULL when memory runs out. */
-static unsigned char *block_table(int N, int n_text, int w, int bm, int bn, int *n_kb_out)
+static unsigned char *block_table(int N, int n_text, int n_img, int image_first, int w, int bm, int bn, int *n_kb_out)
 {
     const int n_qb = (N + bm - 1) / bm, n_kb = (N + bn - 1) / bn;
     unsigned char *t = (unsigned char *)calloc((size_t)n_qb * n_kb, 1);
     if (!t) return NULL;
     for (int i = 0; i < N; ++i)
         for (int j = 0; j < N; ++j)
-            if (difa_oracle_allowed(ORACLE_ARROW, i, j, n_text, w)) t[(size_t)(i / bm) * n_kb + j / bn] = 1;
+            if (difa_oracle_allowed_order(ORACLE_ARROW, i, j, n_text, n_img, w, image_first)) t[(size_t)(i / bm) * n_kb + j / bn] = 1;
     *n_kb_out = n_kb;
     return t;
 }
@@ -103,12 +111,12 @@ int difa_oracle_threads(void)
  * block_m, block_n : 0, 0 for the exact band; otherwise the block sizes of the block-granular band
  * returns 0, -1 on an invalid argument, -2 when host memory runs out.
  */
-int difa_oracle_joint_attention_blocks(const void *q, const void *k, const void *v, const void *cache,
-                                       int dtype, int B, int H, int D,
-                                       const int32_t *head_plan, const int32_t *window,
-                                       int n_text, int n_img, double scale,
-                                       const int32_t *rows, int n_rows, int block_m, int block_n,
-                                       double *out, void *out_raw, double *probs)
+int difa_oracle_joint_attention_order(const void *q, const void *k, const void *v, const void *cache,
+                                      int dtype, int B, int H, int D,
+                                      const int32_t *head_plan, const int32_t *window,
+                                      int n_text, int n_img, int image_first, double scale,
+                                      const int32_t *rows, int n_rows, int block_m, int block_n,
+                                      double *out, void *out_raw, double *probs)
 {
     const int N = n_text + n_img;
     if (!q || !k || !v || !out || !head_plan || B <= 0 || H <= 0 || D <= 0 || N <= 0) return -1;
@@ -151,11 +159,11 @@ int difa_oracle_joint_attention_blocks(const void *q, const void *k, const void 
             unsigned char *blocks = NULL;
             int n_kb = 0;
             if (mode == ORACLE_ARROW && block_m > 0) {
-                blocks = block_table(N, n_text, w, block_m, block_n, &n_kb);
+                blocks = block_table(N, n_text, n_img, image_first, w, block_m, block_n, &n_kb);
                 if (!blocks) return -2;
             }
 #define KEPT(i, j) (blocks ? blocks[(size_t)((i) / block_m) * n_kb + (j) / block_n] \
-                           : difa_oracle_allowed(mode, (i), (j), n_text, w))
+                           : difa_oracle_allowed_order(mode, (i), (j), n_text, n_img, w, image_first))
 
             /* this head's keys and values, widened once (exact) */
             double *kd = (double *)malloc((size_t)N * D * sizeof(double));
@@ -220,6 +228,18 @@ int difa_oracle_joint_attention_blocks(const void *q, const void *k, const void 
         }
     }
     return 0;
+}
+
+/* Text tokens first. */
+int difa_oracle_joint_attention_blocks(const void *q, const void *k, const void *v, const void *cache,
+                                       int dtype, int B, int H, int D,
+                                       const int32_t *head_plan, const int32_t *window,
+                                       int n_text, int n_img, double scale,
+                                       const int32_t *rows, int n_rows, int block_m, int block_n,
+                                       double *out, void *out_raw, double *probs)
+{
+    return difa_oracle_joint_attention_order(q, k, v, cache, dtype, B, H, D, head_plan, window, n_text, n_img, 0,
+                                             scale, rows, n_rows, block_m, block_n, out, out_raw, probs);
 }
 
 /* The exact band (Sec. 3.1). */

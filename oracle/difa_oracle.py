@@ -37,6 +37,15 @@ def lib():
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_double,
             ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.difa_oracle_joint_attention_order.restype = ctypes.c_int
+        L.difa_oracle_joint_attention_order.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double,
+            ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.difa_oracle_allowed_order.restype = ctypes.c_int
+        L.difa_oracle_allowed_order.argtypes = [ctypes.c_int] * 7
         L.difa_oracle_allowed.restype = ctypes.c_int
         L.difa_oracle_allowed.argtypes = [ctypes.c_int] * 5
         L.difa_oracle_threads.restype = ctypes.c_int
@@ -48,19 +57,23 @@ def threads() -> int:
     return int(lib().difa_oracle_threads())
 
 
-def allowed(mode: int, i: int, j: int, n_text: int, w: int) -> bool:
-    """Sec. 3.1: does query i attend to key j for a head in `mode` with half-width w."""
+def allowed(mode: int, i: int, j: int, n_text: int, w: int, n_img: int = 0, image_first: bool = False) -> bool:
+    """Sec. 3.1: does query i attend to key j for a head in `mode` with half-width w.
+    image_first: the text tokens follow the n_img image tokens instead of preceding them."""
+    if image_first:
+        return bool(lib().difa_oracle_allowed_order(int(mode), int(i), int(j), int(n_text), int(n_img), int(w), 1))
     return bool(lib().difa_oracle_allowed(int(mode), int(i), int(j), int(n_text), int(w)))
 
 
 def joint_attention(q, k, v, cache, head_plan, window, n_text, n_img, scale=None,
-                    rows=None, want_probs=False, block=None):
+                    rows=None, want_probs=False, block=None, image_first=False):
     """Evaluate the operator on CPU tensors q, k, v (and cache) of shape [B,H,N,D].
 
     dtype bf16 or fp32; the values are widened exactly to fp64.
     rows: optional 1-D integer sequence of query rows (default: all).
     block: None for the exact band, or (bm, bn) for the block-granular band of Sec. 3.3 / Fig. 4
     (an ARROW head keeps every pair of a bm x bn block that holds a pair of the exact pattern).
+    image_first: the joint sequence is [image tokens, text tokens] instead of [text, image].
     Returns (out_f64 [B,H,R,D], out_raw [B,H,R,D] of the input dtype -- meaningful
     on CACHE heads only, elsewhere zero --, probs [B,H,R,N] or None).
     """
@@ -86,9 +99,9 @@ def joint_attention(q, k, v, cache, head_plan, window, n_text, n_img, scale=None
     out_raw = torch.zeros((B, H, R, D), dtype=q.dtype)
     probs = np.zeros((B, H, R, N), dtype=np.float64) if want_probs else None
     bm, bn = (0, 0) if block is None else (int(block[0]), int(block[1]))
-    rc = lib().difa_oracle_joint_attention_blocks(
+    rc = lib().difa_oracle_joint_attention_order(
         q.data_ptr(), k.data_ptr(), v.data_ptr(), cache.data_ptr() if cache is not None else None,
-        _DT[q.dtype], B, H, D, hp.ctypes.data, win.ctypes.data, int(n_text), int(n_img),
+        _DT[q.dtype], B, H, D, hp.ctypes.data, win.ctypes.data, int(n_text), int(n_img), 1 if image_first else 0,
         float(scale), rows_ptr, R, bm, bn, out.ctypes.data, out_raw.data_ptr(),
         probs.ctypes.data if probs is not None else None)
     if rc != 0:

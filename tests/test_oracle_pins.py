@@ -431,3 +431,85 @@ def test_block_band_covering_window_equals_full():
     q2[:, 1], k2[:, 1], v2[:, 1] = q[:, 0], k[:, 0], v[:, 0]
     full, _, _ = O.joint_attention(q2, k2, v2, None, [ARROW, FULL], [n_img - 1, 0], n_text, n_img, block=(8, 8))
     assert torch.equal(full[:, 0], full[:, 1])
+
+
+# --------------------------------------------------------------------------- image tokens first
+def image_first_rule(n_text, n_img, w):
+    """Sec. 3.1 restated for the order [image, text] with explicit loops."""
+    N = n_text + n_img
+    kept = [[False] * N for _ in range(N)]
+    for i in range(N):
+        for j in range(N):
+            i_text, j_text = i >= n_img, j >= n_img
+            kept[i][j] = i_text or j_text or (-w <= i - j <= w)
+    return kept
+
+
+@pytest.mark.parametrize("n_text,n_img,w", [(0, 12, 2), (4, 16, 1), (7, 9, 3), (3, 20, 0), (16, 8, 5)])
+def test_image_first_matches_brute_force(n_text, n_img, w):
+    # catches: text interval taken at the front, band measured from the wrong origin, text rows not full
+    N, D = n_text + n_img, 4
+    q, k, v = (rand((1, 1, N, D), 500 + s + N) for s in range(3))
+    got, _, probs = O.joint_attention(q, k, v, None, [ARROW], [w], n_text, n_img, scale=0.6, want_probs=True,
+                                      image_first=True)
+    kept = image_first_rule(n_text, n_img, w)
+    ref = brute_force_masked(q[0, 0].tolist(), k[0, 0].tolist(), v[0, 0].tolist(), kept, 0.6)
+    assert (got[0, 0] - ref).abs().max() < 1e-12
+    assert torch.equal(probs[0, 0] > 0, torch.tensor(kept))
+
+
+def test_image_first_is_text_first_with_the_tokens_rotated():
+    # the operator does not care where a token sits, only what kind it is: moving the text block
+    # behind the image block moves the output rows and nothing else
+    n_text, n_img, H, D = 6, 25, 3, 8
+    N = n_text + n_img
+    q, k, v = (rand((2, H, N, D), 600 + s, torch.bfloat16) for s in range(3))
+    hp, win = [ARROW, FULL, ARROW], [3, 0, 9]
+    ref, _, _ = O.joint_attention(q, k, v, None, hp, win, n_text, n_img)
+    rot = list(range(n_text, N)) + list(range(n_text))          # image tokens first, then the text tokens
+    got, _, _ = O.joint_attention(q[:, :, rot], k[:, :, rot], v[:, :, rot], None, hp, win, n_text, n_img,
+                                  image_first=True)
+    assert (got - ref[:, :, rot]).abs().max() < 1e-13
+
+
+def test_image_first_pair_counts_and_predicate():
+    # same number of allowed pairs as with the text in front (hand counts of the golden file)
+    for n_text, n_img, w, pairs in golden_pairs():
+        N = n_text + n_img
+        cnt = sum(O.allowed(ARROW, i, j, n_text, w, n_img=n_img, image_first=True) for i in range(N) for j in range(N))
+        assert cnt == pairs
+    # a few pairs by hand: n_img = 10, n_text = 3, w = 2 -> text tokens are 10, 11, 12
+    a = lambda i, j: O.allowed(ARROW, i, j, 3, 2, n_img=10, image_first=True)
+    assert a(0, 2) and not a(0, 3) and a(0, 10) and a(0, 12)      # band edge; text keys always
+    assert a(9, 7) and not a(9, 6) and a(12, 0) and a(10, 5)      # text queries see everything
+    assert not a(5, 8) and a(5, 7)
+
+
+def test_image_first_text_rows_equal_full_and_covering_window_equals_full():
+    n_text, n_img, D = 5, 18, 8
+    N = n_text + n_img
+    q, k, v = (rand((1, 2, N, D), 700 + s) for s in range(3))
+    full, _, _ = O.joint_attention(q, k, v, None, [FULL, FULL], [0, 0], n_text, n_img, image_first=True)
+    arrow, _, _ = O.joint_attention(q, k, v, None, [ARROW, ARROW], [2, n_img - 1], n_text, n_img, image_first=True)
+    assert torch.equal(arrow[:, 0, n_img:], full[:, 0, n_img:])          # the text rows are the last ones now
+    assert not torch.equal(arrow[:, 0, :n_img], full[:, 0, :n_img])
+    assert torch.equal(arrow[:, 1], full[:, 1])
+
+
+def test_image_first_block_band_matches_brute_force():
+    n_text, n_img, w, bm, bn = 5, 19, 2, 8, 4
+    N, D = n_text + n_img, 4
+    q, k, v = (rand((1, 1, N, D), 800 + s) for s in range(3))
+    got, _, probs = O.joint_attention(q, k, v, None, [ARROW], [w], n_text, n_img, scale=0.7, block=(bm, bn),
+                                      want_probs=True, image_first=True)
+    exact = image_first_rule(n_text, n_img, w)
+    kept = [[False] * N for _ in range(N)]
+    for a in range(0, N, bm):
+        for b in range(0, N, bn):
+            if any(exact[i][j] for i in range(a, min(a + bm, N)) for j in range(b, min(b + bn, N))):
+                for i in range(a, min(a + bm, N)):
+                    for j in range(b, min(b + bn, N)):
+                        kept[i][j] = True
+    ref = brute_force_masked(q[0, 0].tolist(), k[0, 0].tolist(), v[0, 0].tolist(), kept, 0.7)
+    assert (got[0, 0] - ref).abs().max() < 1e-12
+    assert torch.equal(probs[0, 0] > 0, torch.tensor(kept))
