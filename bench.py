@@ -31,13 +31,14 @@ def make_workload(name):
     raise SystemExit(f"unknown workload {name}")
 
 
-def cpu_baseline(wl, q, k, v, cache, every, block=None):
+def cpu_baseline(wl, q, k, v, cache, every, block=None, image_first=False):
     """The oracle as it stands, timed on this host's cores, on every `every`-th query row."""
     from oracle import difa_oracle as O
     from paper_2503_22796_amd.accounting import allowed_pairs
     rows = list(range(0, wl.N, every))
     t0 = time.perf_counter()
-    O.joint_attention(q, k, v, cache, wl.head_plan, wl.window, wl.n_text, wl.n_img, rows=rows, block=block)
+    O.joint_attention(q, k, v, cache, wl.head_plan, wl.window, wl.n_text, wl.n_img, rows=rows, block=block,
+                      image_first=image_first)
     dt = time.perf_counter() - t0
     # FLOPs of exactly the sampled rows (band length depends on the row)
     flops = 0
@@ -132,6 +133,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--block-band", action="store_true",
                     help="arrow heads use the block-granular band of the paper's kernel (Sec. 3.3) instead of the exact one")
+    ap.add_argument("--image-first", action="store_true",
+                    help="joint sequence [image, text] instead of [text, image] (same tokens, rotated)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on one GPU only (heads would be sharded across GPUs, "
@@ -150,10 +153,14 @@ def main():
     wl = make_workload(args.workload)
     q, k, v = W.make_qkv(wl)
     cache0 = W.make_cache(wl)
+    if args.image_first:
+        rot = list(range(wl.n_text, wl.N)) + list(range(wl.n_text))
+        q, k, v, cache0 = (t[:, :, rot].contiguous() for t in (q, k, v, cache0))
     qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)
     bufs = [cache0.to(dev), torch.empty_like(qd)]
     plan = B.difa_plan_create(wl.B, wl.H, wl.D, max_tokens=wl.N,
-                              flags=B.DIFA_FLAG_BLOCK_BAND if args.block_band else 0)
+                              flags=(B.DIFA_FLAG_BLOCK_BAND if args.block_band else 0) |
+                                    (B.DIFA_FLAG_IMAGE_FIRST if args.image_first else 0))
     block = B.difa_tile_shape(wl.D) if args.block_band else None
     fl = plan_flops(wl.head_plan, wl.window, wl.n_text, wl.n_img, wl.D, wl.B, block=block)
     by = plan_bytes(wl.head_plan, wl.n_text, wl.n_img, wl.D, 2, wl.B)
@@ -196,7 +203,8 @@ def main():
                 "frac_of_hbm_peak": rse_bytes / (rse_avg * 1e-3) * 1e-9 / 8000.0 if rse_avg > 0 else None}
 
     bm, bn = B.difa_tile_shape(wl.D)
-    _, items, _ = B.difa_worklist_build(wl.B, wl.H, wl.head_plan, wl.window, wl.n_text, wl.n_img, bm, bn)
+    _, items, _ = B.difa_worklist_build(wl.B, wl.H, wl.head_plan, wl.window, wl.n_text, wl.n_img, bm, bn,
+                                        flags=B.DIFA_FLAG_IMAGE_FIRST if args.image_first else 0)
     items = items[items["q_tile"] >= 0] if items is not None else items
     executed = float(items["n_tiles"].sum()) * bm * bn * 4 * wl.D if items is not None and len(items) else 0.0
 
@@ -229,7 +237,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall_ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": wl.name + ("_block_band" if args.block_band else ""), "batch": wl.B, "heads": wl.H, "head_dim": wl.D,
+        "config": {"workload": wl.name + ("_block_band" if args.block_band else "") + ("_image_first" if args.image_first else ""), "batch": wl.B, "heads": wl.H, "head_dim": wl.D,
                    "n_text": wl.n_text, "n_img": wl.n_img,
                    "plan": {"full": int((wl.head_plan == 0).sum()),
                             "arrow": sorted(int(w) for w in wl.window[wl.head_plan == 1]),
@@ -249,7 +257,8 @@ def main():
     B.difa_plan_destroy(plan)
     if not args.no_cpu and args.cpu_every > 0:
         has_cache = bool((wl.head_plan == 2).any())
-        out["cpu_baseline"] = cpu_baseline(wl, q, k, v, cache0 if has_cache else None, args.cpu_every, block=block)
+        out["cpu_baseline"] = cpu_baseline(wl, q, k, v, cache0 if has_cache else None, args.cpu_every, block=block,
+                                           image_first=args.image_first)
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out))

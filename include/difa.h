@@ -44,8 +44,12 @@ enum { DIFA_LAYOUT_BHND = 0, DIFA_LAYOUT_BNHD = 1 };
  * (Sec. 3.3, Fig. 4: a block that mixes kept and discarded pairs is computed as a dense block, so
  * that only the sequence tail needs masking): an ARROW head then attends to every pair of a (query
  * tile, key tile) block of difa_tile_shape() rows x keys that holds at least one pair of the exact
- * arrow pattern.  Without the flag the band is exact, pair by pair. */
-enum { DIFA_FLAG_BLOCK_BAND = 1u };
+ * arrow pattern.  Without the flag the band is exact, pair by pair.
+ * DIFA_FLAG_IMAGE_FIRST: the joint sequence is [n_img image tokens, n_text text tokens] instead of
+ * [text, image] (the paper says "concatenated" without naming an order, Sec. 2.1 / 3.1; public
+ * MMDiT pipelines use both).  The operator is the same: text queries see every key, image queries
+ * see the text keys and the image keys within the band. */
+enum { DIFA_FLAG_BLOCK_BAND = 1u, DIFA_FLAG_IMAGE_FIRST = 2u };
 
 /* Static description of a layer's attention call; fixed for the life of a plan object. */
 typedef struct {
@@ -114,6 +118,11 @@ const char* difa_last_error(const difa_plan_t* plan);
  * the key tiles the tile must visit, so that masked tiles are never loaded and in-tile masks
  * are applied only where a band edge, the text/image boundary or the sequence end crosses a
  * tile.  Exposed so that it can be checked without a GPU.
+ *
+ * Key tiles are named by their position in an order that starts with the tiles holding text keys:
+ * position u is key tile (u + rot) % n_kv_tiles, n_kv_tiles = ceil(N / bn), where rot = 0 when the
+ * text comes first and rot = n_img / bn with DIFA_FLAG_IMAGE_FIRST (when both kinds of token are
+ * present).  The ranges below are ranges of positions.
  */
 typedef struct {
     int32_t bh;        /* batch * heads + head                                            */
@@ -138,7 +147,7 @@ int32_t difa_tile_shape(int32_t head_dim, int32_t dtype, int32_t* bm, int32_t* b
  *                   n_xcd interleaved queues of equal total cost, heads kept together on a die,
  *                   short queues padded with records whose q_tile is -1.
  *   flags           DIFA_FLAG_BLOCK_BAND: ARROW records visit the same key tiles but carry window -1 and
- *                   need the in-tile mask on the sequence tail only.
+ *                   need the in-tile mask on the sequence tail only.  DIFA_FLAG_IMAGE_FIRST: see above.
  *   items/capacity  HOST array to fill (may be NULL with capacity 0 to only count).
  *   n_items_out     number of records, padding included (written also when capacity is short).
  *   copy_heads/n_copy_out  optional: int32[heads] receiving the indices of CACHE heads.

@@ -16,6 +16,7 @@ DIFA_HEAD_FULL, DIFA_HEAD_ARROW, DIFA_HEAD_CACHE = 0, 1, 2
 DIFA_DTYPE_BF16, DIFA_DTYPE_F32 = 0, 1
 DIFA_LAYOUT_BHND, DIFA_LAYOUT_BNHD = 0, 1
 DIFA_FLAG_BLOCK_BAND = 1
+DIFA_FLAG_IMAGE_FIRST = 2
 
 
 class difa_plan_desc_t(ctypes.Structure):

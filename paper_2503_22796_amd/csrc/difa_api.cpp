@@ -160,7 +160,7 @@ extern "C" difa_status_t difa_plan_create(const difa_plan_desc_t* desc, difa_pla
     if (plan_out) *plan_out = nullptr;
     if (!desc || !plan_out) return fail(nullptr, DIFA_ERR_INVALID_ARG, "desc and plan_out must not be NULL");
     if (desc->batch < 1 || desc->heads < 1 || desc->max_tokens < 1 ||
-        (desc->flags & ~(uint32_t)DIFA_FLAG_BLOCK_BAND) != 0 || desc->device < 0)
+        (desc->flags & ~(uint32_t)(DIFA_FLAG_BLOCK_BAND | DIFA_FLAG_IMAGE_FIRST)) != 0 || desc->device < 0)
         return fail(nullptr, DIFA_ERR_INVALID_ARG, "batch, heads, max_tokens must be >= 1, device >= 0, no unknown flag bits");
     if (!(desc->softmax_scale >= 0.f) || isinf(desc->softmax_scale))
         return fail(nullptr, DIFA_ERR_INVALID_ARG, "softmax_scale must be finite and >= 0 (0 = 1/sqrt(head_dim))");
@@ -168,6 +168,8 @@ extern "C" difa_status_t difa_plan_create(const difa_plan_desc_t* desc, difa_pla
         return fail(nullptr, DIFA_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
     if (desc->dtype != DIFA_DTYPE_BF16 && desc->dtype != DIFA_DTYPE_F32)
         return fail(nullptr, DIFA_ERR_UNSUPPORTED, "dtype must be DIFA_DTYPE_BF16 or DIFA_DTYPE_F32");
+    if (desc->dtype == DIFA_DTYPE_F32 && (desc->flags & DIFA_FLAG_BLOCK_BAND))
+        return fail(nullptr, DIFA_ERR_UNSUPPORTED, "the fp32 debug path evaluates the exact band only (no DIFA_FLAG_BLOCK_BAND)");
     if (desc->layout != DIFA_LAYOUT_BHND && desc->layout != DIFA_LAYOUT_BNHD)
         return fail(nullptr, DIFA_ERR_UNSUPPORTED, "layout must be DIFA_LAYOUT_BHND or DIFA_LAYOUT_BNHD");
 
@@ -431,6 +433,10 @@ extern "C" difa_status_t difa_joint_attention(difa_plan_t* p, const void* q, con
         a.part_ml = p->part_ml;
         a.stride_b = sb; a.stride_h = sh; a.stride_n = sn;
         a.heads = H; a.n_tokens = N; a.n_text = n_text;
+        const bool image_first = (p->desc.flags & DIFA_FLAG_IMAGE_FIRST) != 0;
+        a.text_begin = image_first ? n_img : 0;
+        a.n_kv_tiles = (N + p->bn - 1) / p->bn;
+        a.tile_rot = image_first && n_text > 0 && n_img > 0 ? n_img / p->bn : 0;   // as difa_worklist_build numbers the tiles
         a.scale = p->scale;
         const bool fast = p->desc.dtype == DIFA_DTYPE_BF16;
         // the scratch for cut records is shared by all calls on this object: order them across streams

@@ -24,6 +24,9 @@ struct AttnArgs {
     float* part_ml;                 // device scratch: [slot][kBM][2] row reference (log2 domain), row sum
     int64_t stride_b, stride_h, stride_n;
     int32_t heads, n_tokens, n_text;
+    int32_t text_begin;  // first text token: 0, or n_img when the image tokens come first
+    int32_t tile_rot;    // key-tile position u of a record is tile (u + tile_rot) % n_kv_tiles
+    int32_t n_kv_tiles;
     float scale;  // softmax scale (natural-log domain)
 };
 

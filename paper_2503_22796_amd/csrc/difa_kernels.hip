@@ -123,6 +123,11 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
     const int N = a.n_tokens, n_text = a.n_text;
+    // text tokens are [text_begin, text_begin + n_text), image tokens [img0, img1) (the text block sits
+    // before or after the image block); a record's key-tile position u is tile (u + tile_rot) % n_kv_tiles
+    const int text_begin = a.text_begin;
+    const int img0 = text_begin == 0 ? n_text : 0, img1 = text_begin == 0 ? N : text_begin;
+    auto tile_at = [&](int u) { const int t = u + a.tile_rot; return t >= a.n_kv_tiles ? t - a.n_kv_tiles : t; };
     const float c = a.scale * 1.44269504088896340736f;      // scores are kept in the log2 domain
 
     // ---- per-lane LDS offsets (elements, within one stage)
@@ -195,7 +200,7 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
         for (int t = 0; t < 3; ++t) {
             const int p = sg.pos_begin + t;
-            const int tile = p < sg.kv0_end ? p : sg.kv1_begin + (p - sg.kv0_end);
+            const int tile = tile_at(p < sg.kv0_end ? p : sg.kv1_begin + (p - sg.kv0_end));
             const unsigned tb = t < n ? (unsigned)tile * tile_bytes : 0x80000000u;
             const unsigned st = (unsigned)(((sb + t) & 3) * TILE * 2) + wave_lds;
 #pragma unroll
@@ -253,7 +258,7 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
         i_raw[qb] = row0 + 32 * qb + l32;
         const int i = i_raw[qb] < N ? i_raw[qb] : N - 1;
         int lo, hi;
-        if (it.window < 0 || i < n_text) { lo = 0; hi = N - 1; }
+        if (it.window < 0 || (unsigned)(i - text_begin) < (unsigned)n_text) { lo = 0; hi = N - 1; }
         else { lo = i - it.window; hi = i + it.window < N - 1 ? i + it.window : N - 1; }
         rs[qb].lo = lo;
         rs[qb].span = (unsigned)(hi - lo);                  // key j is in the band iff (unsigned)(j-lo) <= span
@@ -272,12 +277,13 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
     // The segment covers positions [pos_begin, pos_end) of the record's visiting order; idx counts from
     // the segment's first position.
     const int n_iter = it.pos_end - it.pos_begin;
-    auto tile_of = [&](int idx) {
+    auto upos_of = [&](int idx) {                           // key-tile position in the record's rotated order
         const int p = it.pos_begin + (idx < n_iter ? idx : n_iter - 1);   // past the end: reload the last tile (unused)
         return p < it.kv0_end ? p : it.kv1_begin + (p - it.kv0_end);
     };
+    auto tile_of = [&](int idx) { return tile_at(upos_of(idx)); };
     auto tile_masked = [&](int idx) {
-        const int t = tile_of(idx);
+        const int t = upos_of(idx);
         return it.pos_begin + idx < it.kv0_end ? (t >= it.nm0_end) : (t < it.nm1_begin || t >= it.nm1_end);
     };
     auto tile_offset = [&](int idx) {                       // byte offset of the tile at position idx
@@ -305,7 +311,7 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
     const int row_first = it.q_tile * kBM + (int)wave_u * RW;              // this wavefront's rows (uniform)
     const int row_last = row_first + RW - 1 < N - 1 ? row_first + RW - 1 : N - 1;
     auto mask_block = [&](int j0, floatx16 (&s)[QB]) {
-        const bool plain = j0 >= n_text && row_first >= n_text && j0 + 31 < N && it.window >= 0;
+        const bool plain = j0 >= img0 && j0 + 31 < img1 && row_first >= img0 && row_last < img1 && it.window >= 0;
         if (plain) {
             // image rows, image keys, no tail: row i allows keys [i - w, i + w]
             const bool low = row_last - it.window > j0;                    // some row's band starts after j0
@@ -351,7 +357,7 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
             for (int r = 0; r < 16; ++r) {
                 const int j = j0 + 8 * (r >> 2) + 4 * half + (r & 3);
                 // branch-free on purpose: one unsigned range test per segment
-                const bool ok = ((unsigned)j < (unsigned)n_text) | ((unsigned)(j - rs[qb].lo) <= rs[qb].span);
+                const bool ok = ((unsigned)(j - text_begin) < (unsigned)n_text) | ((unsigned)(j - rs[qb].lo) <= rs[qb].span);
                 s[qb][r] = ok ? s[qb][r] : -INFINITY;
             }
     };
@@ -773,13 +779,15 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a) {
     for (int r = 0; r < kBM / 4; ++r) {
         const int i = it.q_tile * kBM + wave * (kBM / 4) + r;
         if (i >= N) break;                                   // uniform over the wavefront
-        // allowed keys: [0, seg0_end) and [lo, hi]
-        int seg0_end, lo, hi;
-        if (it.window < 0 || i < n_text) { seg0_end = 0; lo = 0; hi = N - 1; }
+        // allowed keys: the text keys [seg0_begin, seg0_end) and the image keys [lo, hi]
+        const int tb = a.text_begin, img0 = tb == 0 ? n_text : 0, img1 = tb == 0 ? N : tb;
+        int seg0_begin, seg0_end, lo, hi;
+        if (it.window < 0 || (unsigned)(i - tb) < (unsigned)n_text) { seg0_begin = seg0_end = 0; lo = 0; hi = N - 1; }
         else {
-            seg0_end = n_text;
-            lo = i - it.window > n_text ? i - it.window : n_text;
-            hi = i + it.window < N - 1 ? i + it.window : N - 1;
+            seg0_begin = tb;
+            seg0_end = tb + n_text;
+            lo = i - it.window > img0 ? i - it.window : img0;
+            hi = i + it.window < img1 - 1 ? i + it.window : img1 - 1;
         }
         float qv[D];
 #pragma unroll
@@ -802,7 +810,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a) {
         };
         // pass 1: row maximum
         double m = -INFINITY;
-        for (int j = lane; j < seg0_end; j += 64) m = fmax(m, score(j));
+        for (int j = seg0_begin + lane; j < seg0_end; j += 64) m = fmax(m, score(j));
         for (int j = lo + lane; j <= hi; j += 64) m = fmax(m, score(j));
         m = wave_max(m);
         // pass 2: weights, their sum, and the weighted sum of value rows
@@ -821,7 +829,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a) {
                 acc[d + 2] = fmaf(p, t4[2], acc[d + 2]); acc[d + 3] = fmaf(p, t4[3], acc[d + 3]);
             }
         };
-        for (int j = lane; j < seg0_end; j += 64) accumulate(j);
+        for (int j = seg0_begin + lane; j < seg0_end; j += 64) accumulate(j);
         for (int j = lo + lane; j <= hi; j += 64) accumulate(j);
         l = wave_sum(l);
         float mine = 0.f;                                    // lane d%64 keeps feature d

@@ -15,8 +15,16 @@
 
 namespace {
 
+// Token order: the image tokens are [img0, img1), the text tokens the rest ([0, n_text) when the text
+// comes first, [n_img, n_tokens) when the image does).  Key tiles are numbered in a rotated order that
+// starts at the first tile holding a text key: position u is tile (u + rot) % n_kv_tiles.  With the
+// text in front rot is 0; with the image in front the text tiles still come first in that order, so a
+// record keeps the same two-range form.
 struct Geometry {
     int n_text, n_tokens, bm, bn;
+    int img0, img1;
+    int rot, n_kv_tiles;
+    int tile_at(int u) const { const int t = u + rot; return t >= n_kv_tiles ? t - n_kv_tiles : t; }
 };
 
 // Is there a pair (row in [i0,i1), key in [j0, j0+bn)) that must be masked out?
@@ -25,27 +33,27 @@ bool tile_needs_mask(const Geometry& g, int w, int i0, int i1, int j0) {
     const int j1 = j0 + g.bn;
     if (j1 > g.n_tokens) return true;
     if (w < 0) return false;
-    const int qi0 = std::max(i0, g.n_text), qi1 = i1 - 1;  // image rows [qi0, qi1]
-    const int kj0 = std::max(j0, g.n_text), kj1 = j1 - 1;  // image keys [kj0, kj1]
+    const int qi0 = std::max(i0, g.img0), qi1 = std::min(i1, g.img1) - 1;  // image rows [qi0, qi1]
+    const int kj0 = std::max(j0, g.img0), kj1 = std::min(j1, g.img1) - 1;  // image keys [kj0, kj1]
     if (qi0 > qi1 || kj0 > kj1) return false;
     return (kj1 - qi0 > w) || (qi1 - kj0 > w);
 }
 
-// Mask-free tiles of a range [begin, end): for the first range the mask-free prefix, for the
-// second the longest run of consecutive mask-free tiles.  Treating a mask-free tile as masked
+// Mask-free tiles of a range [begin, end) of positions in the rotated order: for the first range the
+// mask-free prefix, for the second the longest run of consecutive mask-free tiles.  Treating a mask-free tile as masked
 // is always safe, so any sub-run is a valid answer.
 void mask_free_run(const Geometry& g, int w, int i0, int i1, int begin, int end, bool prefix_only,
                    int* run_begin, int* run_end) {
     int best_b = begin, best_e = begin;
     int t = begin;
     while (t < end) {
-        if (tile_needs_mask(g, w, i0, i1, t * g.bn)) {
+        if (tile_needs_mask(g, w, i0, i1, g.tile_at(t) * g.bn)) {
             if (prefix_only) break;
             ++t;
             continue;
         }
         int e = t;
-        while (e < end && !tile_needs_mask(g, w, i0, i1, e * g.bn)) ++e;
+        while (e < end && !tile_needs_mask(g, w, i0, i1, g.tile_at(e) * g.bn)) ++e;
         if (e - t > best_e - best_b) { best_b = t; best_e = e; }
         if (prefix_only) break;
         t = e;
@@ -72,7 +80,7 @@ extern "C" difa_status_t difa_worklist_build(int32_t batch, int32_t heads, const
                                              int32_t* copy_heads, int32_t* n_copy_out) {
     if (!head_plan || !n_items_out || batch < 1 || heads < 1 || n_text < 0 || n_img < 0 ||
         bm < 1 || bn < 1 || n_xcd < 1 || n_xcd > 64 || capacity < 0 || (capacity > 0 && !items) ||
-        (flags & ~(uint32_t)DIFA_FLAG_BLOCK_BAND) != 0)
+        (flags & ~(uint32_t)(DIFA_FLAG_BLOCK_BAND | DIFA_FLAG_IMAGE_FIRST)) != 0)
         return DIFA_ERR_INVALID_ARG;
     const int64_t n64 = (int64_t)n_text + (int64_t)n_img;
     if (n64 < 1 || n64 > (int64_t)1 << 30) return DIFA_ERR_INVALID_ARG;
@@ -82,10 +90,15 @@ extern "C" difa_status_t difa_worklist_build(int32_t batch, int32_t heads, const
             return DIFA_ERR_INVALID_ARG;
         if (mode == DIFA_HEAD_ARROW && (!window || window[h] < 0)) return DIFA_ERR_INVALID_ARG;
     }
-    const Geometry g{n_text, (int)n64, bm, bn};
+    const bool image_first = (flags & DIFA_FLAG_IMAGE_FIRST) != 0 && n_text > 0 && n_img > 0;
+    const int n_kv_tiles = (int)((n64 + bn - 1) / bn);
+    Geometry g{n_text, (int)n64, bm, bn, 0, 0, 0, n_kv_tiles};
+    if (image_first) { g.img0 = 0; g.img1 = n_img; g.rot = n_img / bn; }
+    else if (flags & DIFA_FLAG_IMAGE_FIRST) { g.img0 = 0; g.img1 = n_img; }      // one kind of token only
+    else { g.img0 = n_text; g.img1 = g.n_tokens; }
     const int n_q_tiles = (g.n_tokens + bm - 1) / bm;
-    const int n_kv_tiles = (g.n_tokens + bn - 1) / bn;
-    const int text_tiles = (n_text + bn - 1) / bn;  // tiles that hold at least one text key
+    // tiles that hold at least one text key: the first ones of the rotated order
+    const int text_tiles = image_first ? n_kv_tiles - g.rot : (n_text + bn - 1) / bn;
 
     // Records are first collected head by head (query tiles in ascending order).
     struct HeadSpan { size_t first, count; int64_t cost; };
@@ -112,17 +125,27 @@ extern "C" difa_status_t difa_worklist_build(int32_t batch, int32_t heads, const
                 r.bh = b * heads + h;
                 r.q_tile = qt;
                 r.window = w;
-                if (full) {
+                if (full && !image_first) {
                     r.kv0_end = n_kv_tiles;
                     r.kv1_begin = r.kv1_end = n_kv_tiles;
+                } else if (full || i0 < g.img0 || i1 > g.img1) {
+                    // every key: a full head, or a tile that holds text queries (they see every key).
+                    // (Two ranges when the order is rotated, so that the sequence tail, the one tile a
+                    // full head masks, ends the first range and the image tiles are mask-free as a run.)
+                    r.kv0_end = text_tiles;
+                    r.kv1_begin = text_tiles;
+                    r.kv1_end = n_kv_tiles;
                 } else {
                     r.kv0_end = text_tiles;
-                    if (i0 < n_text) {  // the tile holds text queries: they see every key
-                        r.kv1_begin = text_tiles;
-                        r.kv1_end = n_kv_tiles;
+                    // image keys [lo, hi] that some row of the tile sees, as tiles; the tiles that also hold
+                    // text keys are in the first range already
+                    const int lo = std::max(g.img0, i0 - w);
+                    const int hi = std::min(g.img1 - 1, (i1 - 1) + w);
+                    if (image_first) {
+                        const int t_lo = lo / bn, t_hi = std::min(hi / bn, g.rot - 1);
+                        r.kv1_begin = text_tiles + t_lo;
+                        r.kv1_end = std::max(r.kv1_begin, text_tiles + t_hi + 1);
                     } else {
-                        const int lo = std::max(n_text, i0 - w);
-                        const int hi = std::min(g.n_tokens - 1, (i1 - 1) + w);
                         r.kv1_begin = std::max(text_tiles, lo / bn);
                         r.kv1_end = std::max(r.kv1_begin, hi / bn + 1);
                     }

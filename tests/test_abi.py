@@ -49,7 +49,8 @@ def test_destroy_null_is_ok_and_create_rejects_bad_descriptors():
     assert B.lib.difa_plan_create(None, ctypes.byref(plan)) == B.DIFA_ERR_INVALID_ARG
     assert plan.value is None
     for kw, status in ((dict(batch=0), B.DIFA_ERR_INVALID_ARG), (dict(heads=0), B.DIFA_ERR_INVALID_ARG),
-                       (dict(max_tokens=0), B.DIFA_ERR_INVALID_ARG), (dict(flags=2), B.DIFA_ERR_INVALID_ARG),
+                       (dict(max_tokens=0), B.DIFA_ERR_INVALID_ARG), (dict(flags=4), B.DIFA_ERR_INVALID_ARG),
+                       (dict(flags=1, dtype=1), B.DIFA_ERR_UNSUPPORTED),
                        (dict(softmax_scale=-1.0), B.DIFA_ERR_INVALID_ARG),
                        (dict(head_dim=96), B.DIFA_ERR_UNSUPPORTED), (dict(dtype=7), B.DIFA_ERR_UNSUPPORTED),
                        (dict(layout=5), B.DIFA_ERR_UNSUPPORTED)):

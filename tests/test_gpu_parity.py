@@ -289,3 +289,73 @@ def test_block_band_flux_2k_mixed_sampled_rows():
     wl = W.flux_2k_mixed()
     rows = boundary_rows(wl.n_text, wl.n_img, wl.window[wl.head_plan == ARROW], extra=64, seed=14)
     run_block_case(wl, rows=rows)
+
+
+# ----------------------------------------------------------------------------- image tokens first
+def run_image_first_case(wl, dtype=torch.bfloat16, layout="bhnd", rows=None, block=False):
+    """The workload's tensors with the text block moved behind the image block, DIFA_FLAG_IMAGE_FIRST."""
+    from paper_2503_22796_amd import binding as B
+    rot = list(range(wl.n_text, wl.N)) + list(range(wl.n_text))
+    q, k, v = (t[:, :, rot].contiguous() for t in W.make_qkv(wl, dtype=dtype))
+    cache = W.make_cache(wl, dtype=dtype) if (wl.head_plan == CACHE).any() else None
+    flags = B.DIFA_FLAG_IMAGE_FIRST | (B.DIFA_FLAG_BLOCK_BAND if block else 0)
+    out = gpu_joint_attention(q, k, v, cache, wl.head_plan, wl.window, wl.n_text, wl.n_img, layout=layout, flags=flags)
+    tol = TOL_BF16 if dtype == torch.bfloat16 else TOL_F32
+    blk = B.difa_tile_shape(wl.D) if block else None
+    err = check_against_oracle(out, q, k, v, cache, wl.head_plan, wl.window, wl.n_text, wl.n_img, rows=rows,
+                               tol=tol, block=blk, image_first=True)
+    print(f"{wl.name} (image first{', block band' if block else ''}): dtype={dtype} layout={layout} "
+          f"max_abs_err={err:.3e}", flush=True)
+    return out
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("n_text,n_img,wins", [
+    (16, 64, [8, 16, 70]),         # the tiny shape
+    (0, 700, [0, 1, 70]),          # no text at all
+    (64, 1024, [63, 64, 300]),     # image length a multiple of the key tile
+    (333, 1000, [7, 130, 998]),    # a key tile that holds image and text keys; ragged tail
+    (700, 50, [3, 20, 49]),        # fewer image tokens than one key tile, long text
+    (1, 4099, [0, 255, 2048]),
+])
+def test_image_first_edge_shapes(D, n_text, n_img, wins):
+    wl = small_workload(2, 5, D, n_text, n_img, [FULL, ARROW, ARROW, ARROW, CACHE], [0] + wins + [0], seed=300 + n_img)
+    run_image_first_case(wl)
+
+
+def test_image_first_sd3_1k_all_rows():
+    run_image_first_case(W.sd3_1k())
+
+
+def test_image_first_flux_1k_bnhd_layout():
+    run_image_first_case(W.flux_1k(), layout="bnhd")
+
+
+def test_image_first_flux_2k_mixed_sampled_rows():
+    wl = W.flux_2k_mixed()
+    # edges of the rotated sequence: image rows are 0 .. n_img-1 now, text rows the last n_text
+    rows = sorted({(r - wl.n_text) % wl.N for r in
+                   boundary_rows(wl.n_text, wl.n_img, wl.window[wl.head_plan == ARROW], extra=64, seed=15)})
+    run_image_first_case(wl, rows=rows)
+
+
+def test_image_first_fp32_debug_path():
+    wl = small_workload(1, 4, 64, 40, 300, [FULL, ARROW, ARROW, CACHE], [0, 5, 120, 0], seed=311)
+    run_image_first_case(wl, dtype=torch.float32)
+
+
+def test_image_first_with_block_band():
+    wl = small_workload(2, 4, 128, 100, 1500, [FULL, ARROW, ARROW, ARROW], [0, 7, 130, 700], seed=312)
+    run_image_first_case(wl, block=True)
+
+
+def test_image_first_equals_text_first_on_rotated_inputs():
+    from paper_2503_22796_amd import binding as B
+    wl = small_workload(1, 3, 128, 128, 2048, [FULL, ARROW, ARROW], [0, 100, 600], seed=313)
+    q, k, v = W.make_qkv(wl)
+    ref = gpu_joint_attention(q, k, v, None, wl.head_plan, wl.window, wl.n_text, wl.n_img)
+    rot = list(range(wl.n_text, wl.N)) + list(range(wl.n_text))
+    got = gpu_joint_attention(q[:, :, rot].contiguous(), k[:, :, rot].contiguous(), v[:, :, rot].contiguous(), None,
+                              wl.head_plan, wl.window, wl.n_text, wl.n_img, flags=B.DIFA_FLAG_IMAGE_FIRST)
+    # same pairs, visited in another order: equal up to the rounding of the summation order
+    assert float((got.float() - ref[:, :, rot].float()).abs().max()) <= TOL_BF16

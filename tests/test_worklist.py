@@ -240,4 +240,83 @@ def test_block_band_records_visit_the_same_tiles_and_mask_only_the_tail(n_text, 
             set(range(max(r["nm1_begin"], r["kv1_begin"]), min(r["nm1_end"], r["kv1_end"])))
         ragged_tail = {n_kv - 1} if N % bn else set()
         assert mask_free == visited - ragged_tail
-    assert B.difa_worklist_build(1, H, hp, win, n_text, n_img, bm, bn, 1, flags=6)[0] == B.DIFA_ERR_INVALID_ARG
+    assert B.difa_worklist_build(1, H, hp, win, n_text, n_img, bm, bn, 1, flags=12)[0] == B.DIFA_ERR_INVALID_ARG
+
+
+# --------------------------------------------------------------------------- image tokens first
+def allowed_image_first(mode, w, n_text, n_img, i, j):
+    if mode == FULL:
+        return True
+    return i >= n_img or j >= n_img or abs(i - j) <= w
+
+
+IMAGE_FIRST_CASES = CASES + [
+    (8, 32, 8, 4, [(ARROW, 2), (FULL, 0), (ARROW, 40)]),      # image length a multiple of the key tile
+    (6, 30, 8, 4, [(ARROW, 0), (ARROW, 5)]),                  # a key tile that holds image and text keys
+    (20, 3, 8, 4, [(ARROW, 1)]),                              # fewer image tokens than one key tile
+    (5, 64, 16, 16, [(ARROW, 3), (ARROW, 17), (CACHE, 0)]),
+]
+
+
+@pytest.mark.parametrize("n_text,n_img,bm,bn,heads", IMAGE_FIRST_CASES)
+@pytest.mark.parametrize("n_xcd", [1, 8])
+def test_image_first_records_match_brute_force(n_text, n_img, bm, bn, heads, n_xcd):
+    N = n_text + n_img
+    hp = [m for m, _ in heads]
+    win = [w for _, w in heads]
+    H = len(heads)
+    st, laid, _ = B.difa_worklist_build(1, H, hp, win, n_text, n_img, bm, bn, n_xcd, flags=B.DIFA_FLAG_IMAGE_FIRST)
+    assert st == B.DIFA_OK
+    items = laid[laid["q_tile"] >= 0]
+    T = (N + bn - 1) // bn
+    rot = n_img // bn if (n_text > 0 and n_img > 0) else 0     # position u is tile (u + rot) % T
+    n_q = (N + bm - 1) // bm
+    assert len(items) == sum(1 for m in hp if m != CACHE) * n_q
+    for r in items:
+        h = int(r["bh"])
+        i0, i1 = int(r["q_tile"]) * bm, min(N, (int(r["q_tile"]) + 1) * bm)
+        mode, w = hp[h], win[h]
+        some, every = set(), set()
+        for t in range(T):
+            flags = [(j < N) and allowed_image_first(mode, w, n_text, n_img, i, j)
+                     for i in range(i0, i1) for j in range(t * bn, (t + 1) * bn)]
+            if any(flags):
+                some.add(t)
+            if all(flags):
+                every.add(t)
+        assert 0 <= r["kv0_end"] <= r["kv1_begin"] <= r["kv1_end"] <= T
+        positions = list(range(0, r["kv0_end"])) + list(range(r["kv1_begin"], r["kv1_end"]))
+        visited = {(u + rot) % T for u in positions}
+        assert len(visited) == len(positions) == r["n_tiles"]
+        assert visited == some, "visited tiles must be exactly the tiles that hold an allowed pair"
+        free_pos = list(range(0, min(r["nm0_end"], r["kv0_end"]))) + \
+            list(range(max(r["nm1_begin"], r["kv1_begin"]), min(r["nm1_end"], r["kv1_end"])))
+        mask_free = {(u + rot) % T for u in free_pos}
+        assert mask_free <= every, "a tile flagged mask-free holds a masked pair"
+        # the first range knows only a mask-free prefix: when the first text tile also holds image keys
+        # outside the band, the text tiles behind it are (safely) treated as masked
+        mixed = n_img // bn if (n_img % bn and n_text > 0) else None       # the tile holding image and text keys
+        if mixed is None or mixed in every:
+            assert mask_free == (every & visited), "every mask-free tile should be recognised as such"
+
+
+def test_image_first_flux_2k_shape_tile_counts():
+    bm, bn = B.difa_tile_shape(128)
+    st, items, _ = B.difa_worklist_build(1, 2, [ARROW, FULL], [512, 0], 512, 16384, bm, bn, 8,
+                                         flags=B.DIFA_FLAG_IMAGE_FIRST)
+    assert st == B.DIFA_OK
+    items = items[items["q_tile"] >= 0]
+    T = 16896 // bn
+    full = items[items["window"] == -1]
+    assert (full["n_tiles"] == T).all()
+    arrow = items[items["window"] == 512]
+    mid = arrow[arrow["q_tile"] == 30][0]
+    i0 = 30 * bm
+    lo, hi = i0 - 512, i0 + bm - 1 + 512
+    assert mid["kv0_end"] == 8 and mid["nm0_end"] == 8                      # the 8 text tiles, none masked
+    assert mid["kv1_begin"] == 8 + lo // bn and mid["kv1_end"] == 8 + hi // bn + 1
+    assert mid["n_tiles"] == 8 + (hi // bn - lo // bn + 1)
+    # same cost as with the text in front
+    st, tf, _ = B.difa_worklist_build(1, 2, [ARROW, FULL], [512, 0], 512, 16384, bm, bn, 8)
+    tf = tf[tf["q_tile"] >= 0]
+    assert int(tf["n_tiles"].sum()) == int(items["n_tiles"].sum())

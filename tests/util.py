@@ -43,11 +43,11 @@ def gpu_joint_attention(q, k, v, cache, head_plan, window, n_text, n_img, scale=
 
 
 def check_against_oracle(out, q, k, v, cache, head_plan, window, n_text, n_img, scale=None, rows=None,
-                         tol=TOL_BF16, block=None):
+                         tol=TOL_BF16, block=None, image_first=False):
     """Element-by-element comparison; returns the max abs error over computed heads."""
     from oracle import difa_oracle as O
     ref, ref_raw, _ = O.joint_attention(q, k, v, cache, head_plan, window, n_text, n_img,
-                                        scale=scale, rows=rows, block=block)
+                                        scale=scale, rows=rows, block=block, image_first=image_first)
     got = out if rows is None else out[:, :, list(rows)]
     hp = np.asarray(head_plan)
     worst = 0.0
