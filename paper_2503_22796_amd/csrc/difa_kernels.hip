@@ -33,7 +33,8 @@ __device__ __forceinline__ float halves_sum(float x) {
 // bf16 MFMA attention.
 //
 // A workgroup is 8 / QB wavefronts (QB = 32-row blocks per wavefront; 1 in the shipped build, so eight
-// wavefronts, two per SIMD) and stays resident: it walks the list of segments the host scheduler gave it.  A segment is a 256-row query tile of one (batch, head) together with a
+// wavefronts, two per SIMD) and stays resident: it walks the list of segments the host scheduler gave
+// it.  A segment is a 256-row query tile of one (batch, head) together with a
 // run of that record's key/value tiles (the whole run for most records; a few records are cut so
 // that every workgroup ends at the same time, and their pieces leave fp32 partial results that
 // merge_parts_kernel combines).  Wavefront w owns rows 32*QB*w .. 32*QB*(w+1)-1 as QB 32-row blocks.
@@ -92,7 +93,7 @@ __device__ __forceinline__ void mfma_results_visible() { asm volatile("s_nop 15\
 struct RowState {
     float m;       // reference maximum (log2 domain) the weights are expressed against
     float l;       // running sum of this lane's half of the keys
-    int lo;        // band of allowed image keys is [lo, lo + span]; text keys [0, n_text) always allowed
+    int lo;        // band of allowed image keys is [lo, lo + span]; text keys are always allowed
     unsigned span;
 };
 
