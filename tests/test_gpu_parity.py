@@ -281,8 +281,9 @@ def test_block_band_flux_1k_all_rows_and_it_differs_from_the_exact_band():
     assert any(not torch.equal(out[:, h], exact[:, h]) for h in arrow)      # the flag is not a no-op
     others = [h for h in range(wl.H) if wl.head_plan[h] == FULL]
     # full heads compute the same thing in both runs (their records may be cut at other places, so the
-    # rounding order may differ)
-    assert all(float((out[:, h].float() - exact[:, h].float()).abs().max()) <= TOL_BF16 for h in others)
+    # fp32 sums may differ in the last bits and an output may round to the neighbouring bf16 value:
+    # one bf16 step is 2^-5 for values in [4, 8))
+    assert all(float((out[:, h].float() - exact[:, h].float()).abs().max()) <= 2 * TOL_BF16 for h in others)
 
 
 def test_block_band_flux_2k_mixed_sampled_rows():
