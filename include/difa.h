@@ -93,7 +93,8 @@ difa_status_t difa_plan_create(const difa_plan_desc_t* desc, difa_plan_t** plan_
  * The call enqueues work on `stream` and returns without waiting; host arrays may be freed
  * on return.  Device tensors stay owned by the caller and must stay valid until the stream
  * has run the work.  Calls on one plan object must not be issued from two threads at once.
- * Errors: INVALID_ARG, HIP.  On error nothing has been enqueued.
+ * Errors: INVALID_ARG; UNSUPPORTED when, for bf16, one head's K/V rows span 2 GiB or more in the
+ * plan's layout (32-bit byte offsets inside a head); HIP.  On error nothing has been enqueued.
  */
 difa_status_t difa_joint_attention(difa_plan_t* plan, const void* q, const void* k, const void* v,
                                    void* out, const void* cache, const int32_t* head_plan,

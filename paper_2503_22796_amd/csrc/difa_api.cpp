@@ -326,6 +326,13 @@ extern "C" difa_status_t difa_joint_attention(difa_plan_t* p, const void* q, con
         any_cache |= (mode == DIFA_HEAD_CACHE);
     }
     if (any_cache && !cache) return fail(p, DIFA_ERR_INVALID_ARG, "cache must not be NULL when a head is CACHE");
+    if (p->desc.dtype == DIFA_DTYPE_BF16) {
+        // the bf16 kernel addresses a head's K and V through 32-bit byte offsets (and uses offset 2^31 to
+        // mean "no tile"): the distance from a head's first to its last element must stay below 2 GiB
+        const int64_t row = p->desc.layout == DIFA_LAYOUT_BHND ? D : (int64_t)H * D;
+        if (((n64 - 1) * row + D) * 2 >= ((int64_t)1 << 31))
+            return fail(p, DIFA_ERR_UNSUPPORTED, "one head's K/V spans 2 GiB or more in this layout: too many tokens");
+    }
     hipStream_t stream = (hipStream_t)stream_v;
 
     DeviceGuard guard;

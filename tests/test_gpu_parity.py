@@ -229,6 +229,19 @@ def test_argument_errors_launch_nothing():
         B.difa_plan_destroy(plan)
 
 
+def test_too_many_tokens_for_32_bit_offsets_inside_a_head_are_refused():
+    from paper_2503_22796_amd import binding as B
+    # [B, N, H, D] with 24 heads of 128: a token row is 6 KiB, so 2 GiB of one head is 349 527 tokens
+    plan = B.difa_plan_create(1, 24, 128, layout=B.DIFA_LAYOUT_BNHD, max_tokens=400000)
+    try:
+        t = torch.zeros(1, 64, 24, 128, dtype=torch.bfloat16, device="cuda:0")     # never read: the call is refused
+        with pytest.raises(B.DifaError) as ei:
+            B.difa_joint_attention(plan, t, t, t, torch.empty_like(t), None, [0] * 24, 0, 349600, [0] * 24)
+        assert ei.value.status == B.DIFA_ERR_UNSUPPORTED
+    finally:
+        B.difa_plan_destroy(plan)
+
+
 def test_kernel_timing_hook():
     from paper_2503_22796_amd import binding as B
     wl = small_workload(1, 4, 128, 64, 1024, [FULL, ARROW, CACHE, FULL], [0, 100, 0, 0], seed=121)
