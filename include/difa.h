@@ -229,11 +229,13 @@ difa_status_t difa_head_rse(difa_plan_t* plan, const void* y_m, const void* y_o,
  * (The printed objective lists the method latencies only; a head without a method is priced at
  * latency_full here, without which the minimum would be "choose nothing".)
  *   influence   host, heads x n_methods, row-major, >= 0: the values difa_head_rse produced per method.
- *   latency     host, n_methods values >= 0; latency_full >= 0: cost of one head under each method.
+ *               +inf is accepted (such a method is never chosen for that head); NaN is rejected.
+ *   latency     host, n_methods finite values >= 0; latency_full finite, >= 0: cost of one head under
+ *               each method.
  *   choice_out  host, heads entries: the method index chosen for each head, -1 = full attention.
  *   total_latency_out, total_influence_out  host, may be NULL.
  * Among several optimal assignments one is returned.  Returns DIFA_OK, INVALID_ARG (NULL pointers,
- * negative or NaN values), ALLOC, or UNSUPPORTED when the search frontier outgrows 2^20 entries.
+ * negative or NaN values, infinite latencies), ALLOC, or UNSUPPORTED when the search frontier outgrows 2^20 entries.
  */
 difa_status_t difa_plan_solve(const double* influence, const double* latency, double latency_full,
                               int32_t heads, int32_t n_methods, double delta, double c,

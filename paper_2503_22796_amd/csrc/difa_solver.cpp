@@ -8,6 +8,7 @@
 // frontier is kept sorted by influence, so pruning is one pass.  Each frontier entry remembers its
 // predecessor and its head's choice, which gives the assignment back at the end.
 #include <algorithm>
+#include <cmath>
 #include <cstdint>
 #include <new>
 #include <vector>
@@ -32,11 +33,14 @@ extern "C" difa_status_t difa_plan_solve(const double* influence, const double* 
                                          int32_t* choice_out, double* total_latency_out,
                                          double* total_influence_out) {
     if (!influence || !latency || !choice_out || heads < 1 || n_methods < 1) return DIFA_ERR_INVALID_ARG;
-    if (!(delta >= 0.0) || !(c >= 0.0) || !(latency_full >= 0.0)) return DIFA_ERR_INVALID_ARG;
+    // (this file is compiled with IEEE comparisons: a NaN fails every test below.  An influence of +inf
+    // is legal -- the metric of a head whose original output is constant -- and is never chosen;
+    // latencies must be finite, or the total would not be a number.)
+    if (!(delta >= 0.0) || !(c >= 0.0) || !(latency_full >= 0.0) || std::isinf(latency_full)) return DIFA_ERR_INVALID_ARG;
     for (int64_t i = 0; i < (int64_t)heads * n_methods; ++i)
-        if (!(influence[i] >= 0.0)) return DIFA_ERR_INVALID_ARG;
+        if (std::isnan(influence[i]) || !(influence[i] >= 0.0)) return DIFA_ERR_INVALID_ARG;
     for (int32_t m = 0; m < n_methods; ++m)
-        if (!(latency[m] >= 0.0)) return DIFA_ERR_INVALID_ARG;
+        if (std::isnan(latency[m]) || !(latency[m] >= 0.0) || std::isinf(latency[m])) return DIFA_ERR_INVALID_ARG;
     const double cap = c / (double)heads * delta;
 
     try {

@@ -88,3 +88,35 @@ def test_limits_and_bad_arguments():
     st, *_ = B.difa_plan_solve(np.array([[-0.1]]), [1.0], 10.0, 1.0, 1.0)
     assert st == B.DIFA_ERR_INVALID_ARG
     assert B.lib.difa_plan_solve(None, None, 1.0, 1, 1, 1.0, 1.0, None, None, None) == B.DIFA_ERR_INVALID_ARG
+
+
+def test_nan_and_infinity_inside_the_arrays():
+    """NaN anywhere is an error; an infinite influence is a method that is never chosen; latencies are finite."""
+    from paper_2503_22796_amd import binding as B
+    infl = np.array([[0.2, 0.5], [0.1, 0.4]])
+    lat = [3.0, 1.0]
+    for h in range(2):
+        for m in range(2):
+            bad = infl.copy()
+            bad[h, m] = float("nan")
+            st, *_ = B.difa_plan_solve(bad, lat, 10.0, 1.0, 2.0)
+            assert st == B.DIFA_ERR_INVALID_ARG, (h, m)
+    for m in range(2):
+        for val in (float("nan"), float("inf"), -1.0):
+            bad = list(lat)
+            bad[m] = val
+            st, *_ = B.difa_plan_solve(infl, bad, 10.0, 1.0, 2.0)
+            assert st == B.DIFA_ERR_INVALID_ARG, (m, val)
+    for val in (float("inf"), float("nan")):
+        assert B.difa_plan_solve(infl, lat, val, 1.0, 2.0)[0] == B.DIFA_ERR_INVALID_ARG
+    assert B.difa_plan_solve(infl, lat, 10.0, float("nan"), 2.0)[0] == B.DIFA_ERR_INVALID_ARG
+    assert B.difa_plan_solve(infl, lat, 10.0, 1.0, float("nan"))[0] == B.DIFA_ERR_INVALID_ARG
+    # +inf influence: legal, that (head, method) is simply unavailable
+    inf_case = np.array([[float("inf"), 0.5], [0.1, float("inf")]])
+    st, choice, tl, ti = B.difa_plan_solve(inf_case, lat, 10.0, 1.0, 2.0)
+    assert st == B.DIFA_OK and list(choice) == [1, 0] and tl == 4.0 and abs(ti - 0.6) < 1e-12
+    best, _ = P.solve(inf_case.tolist(), lat, 10.0, 1.0, 2.0)
+    assert best == tl
+    all_inf = np.full((2, 2), float("inf"))
+    st, choice, tl, ti = B.difa_plan_solve(all_inf, lat, 10.0, 1.0, 2.0)
+    assert st == B.DIFA_OK and list(choice) == [-1, -1] and tl == 20.0 and ti == 0.0
