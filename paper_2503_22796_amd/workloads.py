@@ -10,7 +10,8 @@ image-image block that is local around the diagonal, heads that differ from glob
 to very local, and an arbitrary text block.
 
 Layout everywhere: [B, H, N, D], N = n_text + n_img, text tokens first, image token
-(y, x) of a G x G grid at index n_text + y*G + x.
+(y, x) of a Gy x Gx latent grid at index n_text + y*Gx + x (a video latent adds a leading
+frame axis: (f, y, x) at n_text + (f*Gy + y)*Gx + x).
 """
 from dataclasses import dataclass, field
 import math
@@ -33,6 +34,7 @@ class Workload:
     window: np.ndarray
     seed: int
     positional: bool = True
+    grid: tuple = None          # latent grid (Gy, Gx) or (frames, Gy, Gx); None: the most nearly square Gy x Gx
     notes: str = ""
     extra: dict = field(default_factory=dict)
 
@@ -45,25 +47,35 @@ class Workload:
         return 1.0 / math.sqrt(self.D)
 
 
-def positional_term(n_img: int, D: int, amplitude: float = 1.5) -> np.ndarray:
-    """Smooth 2-D sinusoidal term [n_img, D] shared by every head and batch entry.
+def default_grid(n_img: int) -> tuple:
+    """The most nearly square (Gy, Gx) with Gy * Gx = n_img and Gy <= Gx."""
+    gy = int(math.isqrt(n_img))
+    while n_img % gy:
+        gy -= 1
+    return (gy, n_img // gy)
 
-    Frequencies run from a period of 2 tokens to a period of 2G tokens, alternating
-    sin/cos of the row and of the column, so that q.k between two image tokens peaks
-    when they are close on the grid.
+
+def positional_term(n_img: int, D: int, amplitude: float = 1.5, grid: tuple = None) -> np.ndarray:
+    """Smooth sinusoidal term [n_img, D] shared by every head and batch entry.
+
+    Per grid axis of extent G, frequencies run from a period of 2 tokens to a period of 2G tokens;
+    the features alternate sin/cos of each axis coordinate, so that q.k between two image tokens peaks
+    when they are close on the grid.  With k axes the first (D // 2k) * 2k features carry the term, the
+    rest stay zero.
     """
-    G = int(round(math.sqrt(n_img)))
-    assert G * G == n_img and D % 4 == 0
-    nk = D // 4
+    grid = tuple(int(g) for g in (grid if grid is not None else default_grid(n_img)))
+    k = len(grid)
+    assert k in (2, 3) and int(np.prod(grid)) == n_img and D >= 2 * k
+    nk = D // (2 * k)
     kk = np.arange(nk, dtype=np.float64)
-    omega = np.pi / np.power(float(G), kk / max(nk - 1, 1))
-    y = np.repeat(np.arange(G, dtype=np.float64), G)[:, None]
-    x = np.tile(np.arange(G, dtype=np.float64), G)[:, None]
-    pos = np.empty((n_img, D), dtype=np.float64)
-    pos[:, 0::4] = np.sin(omega * y)
-    pos[:, 1::4] = np.cos(omega * y)
-    pos[:, 2::4] = np.sin(omega * x)
-    pos[:, 3::4] = np.cos(omega * x)
+    coords = np.stack(np.meshgrid(*[np.arange(g, dtype=np.float64) for g in grid], indexing="ij"), axis=-1)
+    coords = coords.reshape(n_img, k)                      # row-major flattening: the last axis moves fastest
+    pos = np.zeros((n_img, D), dtype=np.float64)
+    for ax, G in enumerate(grid):
+        omega = np.pi / np.power(float(max(G, 2)), kk / max(nk - 1, 1))
+        c = coords[:, ax:ax + 1]
+        pos[:, 2 * ax:2 * k * nk:2 * k] = np.sin(omega * c)
+        pos[:, 2 * ax + 1:2 * k * nk:2 * k] = np.cos(omega * c)
     return (amplitude * pos).astype(np.float32)
 
 
@@ -77,7 +89,7 @@ def make_qkv(wl: Workload, step: int = 0, dtype=torch.bfloat16):
     """Q, K, V = N(0,1) (+ the positional term on image tokens), rounded to `dtype`."""
     shape = (wl.B, wl.H, wl.N, wl.D)
     outs = []
-    pos = positional_term(wl.n_img, wl.D) if (wl.positional and wl.n_img > 0) else None
+    pos = positional_term(wl.n_img, wl.D, grid=wl.grid) if (wl.positional and wl.n_img > 0) else None
     for t in range(3):
         a = _normal(wl.seed, 16 * step + t, shape)
         if pos is not None:
