@@ -101,6 +101,26 @@ difa_status_t difa_joint_attention(difa_plan_t* plan, const void* q, const void*
                                    int32_t n_text, int32_t n_img, const int32_t* window,
                                    void* stream);
 
+/*
+ * The same operator for callers that cannot allocate device memory or let a library do so on their
+ * behalf while they run: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Arguments, result, asynchrony and errors are those of difa_joint_attention.  The only
+ * difference: the partial results of work records that the schedule cuts into pieces are kept in a
+ * device array that is part of the library's code object (68 157 440 bytes per GPU, there from the
+ * moment the library is loaded until the process ends) instead of the plan object's own buffer.  The
+ * call makes no hipMalloc / hipFree and calls no allocating library routine.
+ * Limit: a call whose schedule needs more than the array holds -- pieces * 256 rows * (head_dim + 2)
+ * floats; 512 pieces at head_dim 128, which covers every schedule for a GPU of up to 256 compute
+ * units -- fails with DIFA_ERR_UNSUPPORTED and a message naming both sizes.
+ * Every call of this entry point on one GPU uses the same array, whatever the plan object or stream:
+ * two such calls that overlap in time on one GPU race and produce wrong rows; the caller orders them
+ * (one stream, or events).  Calls of difa_joint_attention are not affected by it.
+ */
+difa_status_t difa_joint_attention_static(difa_plan_t* plan, const void* q, const void* k, const void* v,
+                                          void* out, const void* cache, const int32_t* head_plan,
+                                          int32_t n_text, int32_t n_img, const int32_t* window,
+                                          void* stream);
+
 /* Release the object and its buffers (waits for the device to finish work that uses them).
  * NULL is a no-op that returns DIFA_OK. */
 difa_status_t difa_plan_destroy(difa_plan_t* plan);

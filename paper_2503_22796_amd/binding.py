@@ -51,6 +51,8 @@ def _load():
     L.difa_plan_create.argtypes = [ctypes.POINTER(difa_plan_desc_t), ctypes.POINTER(vp)]
     L.difa_joint_attention.restype = ctypes.c_int
     L.difa_joint_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp]
+    L.difa_joint_attention_static.restype = ctypes.c_int
+    L.difa_joint_attention_static.argtypes = L.difa_joint_attention.argtypes
     L.difa_plan_destroy.restype = ctypes.c_int
     L.difa_plan_destroy.argtypes = [vp]
     L.difa_status_string.restype = ctypes.c_char_p
@@ -171,7 +173,13 @@ def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
-def difa_joint_attention(plan, q, k, v, out, cache, head_plan, n_text, n_img, window, stream=None):
+def difa_joint_attention_static(plan, q, k, v, out, cache, head_plan, n_text, n_img, window, stream=None):
+    """difa_joint_attention with the library's file-scope device array as scratch (no allocation anywhere)."""
+    return difa_joint_attention(plan, q, k, v, out, cache, head_plan, n_text, n_img, window, stream=stream,
+                                _entry=lib.difa_joint_attention_static)
+
+
+def difa_joint_attention(plan, q, k, v, out, cache, head_plan, n_text, n_img, window, stream=None, _entry=None):
     """q, k, v, out, cache: torch tensors on the plan's device (cache may be None).
 
     `stream`: a torch.cuda.Stream, a raw hipStream_t integer, or None for torch's current stream.
@@ -182,7 +190,7 @@ def difa_joint_attention(plan, q, k, v, out, cache, head_plan, n_text, n_img, wi
         stream = torch.cuda.current_stream(q.device).cuda_stream
     elif hasattr(stream, "cuda_stream"):
         stream = stream.cuda_stream
-    st = lib.difa_joint_attention(plan, _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(cache),
+    st = (_entry or lib.difa_joint_attention)(plan, _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(cache),
                                   hp.ctypes.data if hp is not None else None, int(n_text), int(n_img),
                                   win.ctypes.data if win is not None else None, ctypes.c_void_p(stream))
     if st != DIFA_OK:

@@ -20,7 +20,7 @@ struct Slot {
     std::vector<int32_t> key;
     void* h_buf = nullptr;  // pinned host staging: CACHE-head indices, then the work records
     void* d_buf = nullptr;  // device copy
-    int32_t n_items = 0, n_copy = 0, n_merges = 0;
+    int32_t n_items = 0, n_copy = 0, n_merges = 0, n_slots = 0;
     size_t wg_off = 0, segs_off = 0, merges_off = 0, items_off = 0;  // byte offsets inside the buffers
     hipEvent_t uploaded = nullptr;  // recorded after the host-to-device copy
     hipEvent_t last_use = nullptr;  // recorded after the last launch that reads d_buf
@@ -207,6 +207,8 @@ extern "C" difa_status_t difa_plan_create(const difa_plan_desc_t* desc, difa_pla
     DeviceGuard guard;
     e = guard.enter(desc->device);
     if (e != hipSuccess) { delete p; return fail(nullptr, DIFA_ERR_HIP, hip_msg("hipSetDevice", e)); }
+    e = difa::static_scratch_init(desc->device);   // device address of the file-scope scratch, once per device
+    if (e != hipSuccess) { delete p; return fail(nullptr, DIFA_ERR_HIP, hip_msg("hipGetSymbolAddress(static scratch)", e)); }
     if (desc->dtype == DIFA_DTYPE_BF16) {
         const size_t slots = 2 * (size_t)p->n_wg;
         e = hipMalloc((void**)&p->part_o, slots * (size_t)p->bm * desc->head_dim * sizeof(float));
@@ -301,10 +303,14 @@ extern "C" difa_status_t difa_plan_timing_read_head_rse(difa_plan_t* p, double* 
     return DIFA_OK;
 }
 
-extern "C" difa_status_t difa_joint_attention(difa_plan_t* p, const void* q, const void* k, const void* v,
-                                              void* out, const void* cache, const int32_t* head_plan,
-                                              int32_t n_text, int32_t n_img, const int32_t* window,
-                                              void* stream_v) {
+namespace {
+
+// The body of both attention entry points.  static_scratch: partial results of cut records go to the
+// library's file-scope device array instead of the plan's own buffer.
+difa_status_t joint_attention_impl(difa_plan_t* p, const void* q, const void* k, const void* v,
+                                   void* out, const void* cache, const int32_t* head_plan,
+                                   int32_t n_text, int32_t n_img, const int32_t* window,
+                                   void* stream_v, bool static_scratch) {
     if (!p) return DIFA_ERR_INVALID_ARG;
     if (!q || !k || !v || !out || !head_plan)
         return fail(p, DIFA_ERR_INVALID_ARG, "q, k, v, out and head_plan must not be NULL");
@@ -388,6 +394,7 @@ extern "C" difa_status_t difa_joint_attention(difa_plan_t* p, const void* q, con
         if (e == hipSuccess) e = hipEventRecord(lru->uploaded, stream);
         if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("uploading the work list", e));
         lru->n_merges = n_merges;
+        lru->n_slots = n_slots;
         lru->key = key;
         lru->n_items = n_items;
         lru->n_copy = n_copy;
@@ -438,6 +445,22 @@ extern "C" difa_status_t difa_joint_attention(difa_plan_t* p, const void* q, con
         a.merges = (const difa_merge_item_t*)(db + slot->merges_off);
         a.part_o = p->part_o;
         a.part_ml = p->part_ml;
+        if (static_scratch && p->desc.dtype == DIFA_DTYPE_BF16 && slot->n_slots > 0) {
+            // [n_slots][bm][head_dim] accumulators, then [n_slots][bm][2] row references and sums
+            size_t cap = 0;
+            float* base = difa::static_scratch(p->desc.device, &cap);
+            const size_t o_floats = (size_t)slot->n_slots * p->bm * D, ml_floats = (size_t)slot->n_slots * p->bm * 2;
+            if (!base)
+                return fail(p, DIFA_ERR_HIP, "the static scratch array has no address on this device (set up in difa_plan_create)");
+            if ((o_floats + ml_floats) * sizeof(float) > cap) {
+                char msg[200];
+                snprintf(msg, sizeof msg, "difa_joint_attention_static: this call needs %zu bytes of scratch for %d cut-record "
+                         "pieces, the static array holds %zu", (o_floats + ml_floats) * sizeof(float), slot->n_slots, cap);
+                return fail(p, DIFA_ERR_UNSUPPORTED, msg);
+            }
+            a.part_o = base;
+            a.part_ml = base + o_floats;
+        }
         a.stride_b = sb; a.stride_h = sh; a.stride_n = sn;
         a.heads = H; a.n_tokens = N; a.n_text = n_text;
         const bool image_first = (p->desc.flags & DIFA_FLAG_IMAGE_FIRST) != 0;
@@ -470,6 +493,30 @@ extern "C" difa_status_t difa_joint_attention(difa_plan_t* p, const void* q, con
     slot->used = true;
     if (p->timing && p->pending.size() > 512) (void)timing_flush(p);
     return DIFA_OK;
+}
+
+}  // namespace
+
+extern "C" difa_status_t difa_joint_attention(difa_plan_t* p, const void* q, const void* k, const void* v,
+                                              void* out, const void* cache, const int32_t* head_plan,
+                                              int32_t n_text, int32_t n_img, const int32_t* window,
+                                              void* stream) {
+    try {
+        return joint_attention_impl(p, q, k, v, out, cache, head_plan, n_text, n_img, window, stream, false);
+    } catch (const std::bad_alloc&) {
+        return fail(p, DIFA_ERR_ALLOC, "out of host memory");
+    }
+}
+
+extern "C" difa_status_t difa_joint_attention_static(difa_plan_t* p, const void* q, const void* k, const void* v,
+                                                     void* out, const void* cache, const int32_t* head_plan,
+                                                     int32_t n_text, int32_t n_img, const int32_t* window,
+                                                     void* stream) {
+    try {
+        return joint_attention_impl(p, q, k, v, out, cache, head_plan, n_text, n_img, window, stream, true);
+    } catch (const std::bad_alloc&) {
+        return fail(p, DIFA_ERR_ALLOC, "out of host memory");
+    }
 }
 
 // Influence[h] = RSE(O[h], O'[h]) of Alg. 1 (Sec. 3.4.1, Eq. 1): one streaming pass over both tensors.

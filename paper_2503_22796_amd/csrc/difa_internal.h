@@ -55,4 +55,10 @@ hipError_t launch_attn_f32(const AttnArgs& a, int head_dim, int n_items, hipStre
 hipError_t launch_cache_copy(const CopyArgs& a, hipStream_t stream);
 hipError_t launch_head_rse(const RseArgs& a, int dtype, hipStream_t stream);
 
+// File-scope device scratch of difa_joint_attention_static (defined beside the kernels that use it).
+// static_scratch_init: looks up the array's address on `device`, which must be the current device; once per
+// device, later calls return at once.  static_scratch: that address (NULL before init) and the array's size.
+hipError_t static_scratch_init(int device);
+float* static_scratch(int device, size_t* bytes);
+
 }  // namespace difa

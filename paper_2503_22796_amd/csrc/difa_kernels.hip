@@ -2,6 +2,7 @@
 //   attn_bf16_kernel  -- full / arrow heads, bf16 MFMA with fp32 accumulation
 //   attn_f32_kernel   -- the same result in plain fp32 arithmetic (slow debug path)
 //   cache_copy_kernel -- cached heads: out[b,h] = cache[b,h] (Alg. 1, last statement)
+#include <mutex>
 #include <type_traits>
 
 #include "difa_internal.h"
@@ -724,6 +725,39 @@ __global__ __launch_bounds__(256) void merge_parts_kernel(AttnArgs a) {
         for (int t = 0; t < 8; ++t) w8[t] = (__bf16)(acc[t] * inv);
         *(bf16x8*)(og + (int64_t)i * a.stride_n + 8 * ch) = w8;
     }
+}
+
+// ------------------------------------------------------------------------------------------
+// Scratch of difa_joint_attention_static, the entry point for callers that must not allocate: the
+// partial results of cut records (what part_o / part_ml point at) live in this file-scope array
+// instead of a buffer the plan object allocated.  512 pieces of 256 rows at head_dim 128:
+// 512 * 256 * (128 + 2) floats = 68 157 440 bytes, held by every GPU the library runs on until the
+// process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the device
+// address is looked up once per device and is what the kernels receive as an argument.
+// ------------------------------------------------------------------------------------------
+constexpr size_t kStaticScratchFloats = (size_t)512 * kBM * (128 + 2);
+static __device__ __align__(256) float scratch[kStaticScratchFloats];
+constexpr int kMaxDevices = 64;
+static float* g_scratch_ptr[kMaxDevices];      // device address of `scratch` per device ordinal
+static std::mutex g_scratch_mutex;
+
+hipError_t static_scratch_init(int device) {
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[device]) return hipSuccess;
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));   // of the current device's copy
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[device] = (float*)ptr;
+    return hipSuccess;
+}
+
+float* static_scratch(int device, size_t* bytes) {
+    if (bytes) *bytes = kStaticScratchFloats * sizeof(float);
+    if (device < 0 || device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    return g_scratch_ptr[device];
 }
 
 // 32-row blocks per wavefront (the kernel's QB).  1: eight wavefronts per workgroup, two per SIMD, so that
