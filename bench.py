@@ -185,8 +185,8 @@ def main():
         step(i)
     attn_ms, copy_ms, launches = B.difa_plan_timing_read(plan)
     B.difa_plan_timing_enable(plan, False)
-    attn_avg = attn_ms / max(launches, 1)
-    copy_avg = copy_ms / max(args.steps, 1)
+    attn_avg = attn_ms / max(launches, 1)       # the one launch of a call: attention and the cached-head copy
+    copy_avg = attn_avg if not fl["computed"] else 0.0   # a layer with every head cached is the copy alone
 
     # calibration helper (Sec. 3.4.1): the per-head influence metric of this layer's two output buffers,
     # an HBM-bound streaming pass over both

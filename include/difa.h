@@ -188,7 +188,8 @@ difa_status_t difa_worklist_build(int32_t batch, int32_t heads, const int32_t* h
  * the first range, then those of the second).  Most segments are whole records; to give every
  * compute unit the same amount of work, some records are cut into several segments that different
  * workgroups execute, each leaving an unnormalised partial result (fp32 O, row reference, row sum)
- * in a scratch slot; a short second kernel merges the slots of a record and writes its rows.
+ * in a scratch slot; the workgroup that finishes its piece last folds the other pieces' slots into
+ * its own result and writes the record's rows.
  */
 typedef struct {
     int32_t bh, q_tile;          /* as in the record                                                  */
@@ -196,6 +197,11 @@ typedef struct {
     int32_t pos_begin, pos_end;  /* positions [pos_begin, pos_end) of the record's visiting order      */
     int32_t part_slot;           /* -1: the segment is the whole record and writes `out`; otherwise
                                     the scratch slot that receives the partial result                 */
+    int32_t merge_idx;           /* index of the record's difa_merge_item_t, -1 for a whole record     */
+    int32_t n_parts;             /* number of pieces the record was cut into (1 for a whole record)    */
+    int32_t first_slot;          /* scratch slot of the record's first piece (its pieces use consecutive
+                                    slots), -1 for a whole record                                      */
+    int32_t reserved;            /* 0; the record is 64 bytes                                          */
 } difa_segment_t;
 
 typedef struct {
@@ -262,9 +268,10 @@ difa_status_t difa_plan_solve(const double* influence, const double* latency, do
                               int32_t* choice_out, double* total_latency_out, double* total_influence_out);
 
 /* ------------------------------------------------------------------ measurement hooks
- * With timing enabled the library brackets its attention kernel (not the cache copy) with
- * HIP events on the caller's stream; difa_plan_timing_read waits for the last bracket and
- * returns the accumulated kernel milliseconds and launch count since the last reset.
+ * With timing enabled the library brackets its kernel launches with HIP events on the caller's
+ * stream; difa_plan_timing_read waits for the last bracket and returns the accumulated kernel
+ * milliseconds and launch count since the last reset.  attn_ms: the layer kernel (on the bf16 path it
+ * holds the cached-head copy as well); copy_ms: the separate copy kernel of the fp32 debug path.
  */
 difa_status_t difa_plan_timing_enable(difa_plan_t* plan, int32_t enable);
 difa_status_t difa_plan_timing_read(difa_plan_t* plan, double* attn_ms, double* copy_ms,

@@ -34,7 +34,7 @@ class difa_work_item_t(ctypes.Structure):
 class difa_segment_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("bh", "q_tile", "kv0_end", "nm0_end", "kv1_begin", "kv1_end", "nm1_begin", "nm1_end",
-                 "window", "pos_begin", "pos_end", "part_slot")]
+                 "window", "pos_begin", "pos_end", "part_slot", "merge_idx", "n_parts", "first_slot", "reserved")]
 
 
 class difa_merge_item_t(ctypes.Structure):

@@ -1,6 +1,7 @@
 // Host side of the C ABI: argument checking, the per-plan memo of compiled work lists, and
 // the launches.  The operator is Sec. 3.3 of the paper (per-head full / arrow / cached
 // output, cached heads filled as in the last statement of Alg. 1).
+#include <limits.h>
 #include <math.h>
 #include <stdio.h>
 #include <string.h>
@@ -13,20 +14,22 @@
 
 namespace {
 
-constexpr int kSlots = 8;  // distinct (head plan, n_text, n_img) work lists kept resident
-constexpr int kXcd = 8;    // accelerator dies of an MI355X: workgroup p runs on die p % 8
+constexpr int kSlots = 8;      // distinct (head plan, n_text, n_img) schedules kept resident on the device
+constexpr int kStagings = 16;  // pinned host buffers the schedules are uploaded from, used in turn
+constexpr int kXcd = 8;        // accelerator dies of an MI355X: workgroup p runs on die p % 8
 
 struct Slot {
-    std::vector<int32_t> key;
-    void* h_buf = nullptr;  // pinned host staging: CACHE-head indices, then the work records
-    void* d_buf = nullptr;  // device copy
+    void* d_buf = nullptr;  // device: CACHE-head indices, then the schedule (or the debug path's work records)
     int32_t n_items = 0, n_copy = 0, n_merges = 0, n_slots = 0;
-    size_t wg_off = 0, segs_off = 0, merges_off = 0, items_off = 0;  // byte offsets inside the buffers
-    hipEvent_t uploaded = nullptr;  // recorded after the host-to-device copy
-    hipEvent_t last_use = nullptr;  // recorded after the last launch that reads d_buf
-    hipStream_t upload_stream = nullptr;
-    bool valid = false, used = false;
+    size_t wg_off = 0, segs_off = 0, merges_off = 0, items_off = 0;  // byte offsets inside the buffer
+    bool valid = false;
     uint64_t stamp = 0;
+};
+
+struct Staging {
+    void* h_buf = nullptr;        // pinned host memory
+    hipEvent_t copied = nullptr;  // recorded behind the host-to-device copy that reads h_buf
+    bool pending = false;         // such a copy has been issued
 };
 
 struct TimingPair {
@@ -42,18 +45,23 @@ struct difa_plan {
     int32_t bm, bn;
     int32_t item_capacity;
     int32_t n_wg, n_xcd;           // persistent workgroups (one per compute unit), accelerator dies
-    size_t buf_bytes, heads_bytes; // slot buffer: cached-head list, then the schedule
+    size_t buf_bytes, heads_bytes; // schedule buffer: cached-head list, then the schedule
     float* part_o = nullptr;       // device scratch for records cut into pieces: 2 * n_wg slots
     float* part_ml = nullptr;
-    hipEvent_t last_launch = nullptr;   // after the last attention launch (the scratch is shared by all calls)
-    hipStream_t last_stream = nullptr;
+    int32_t* ctl = nullptr;        // device: one ticket per cut record; zero between launches
+    double* rse_part = nullptr;    // device scratch of difa_head_rse: batch * heads * kRseChunks * 3 sums
+    // Everything the object enqueues is kept in one order, whatever streams the calls name: the scratch
+    // buffers, the counters and the schedule buffers are shared by all of them.  While the calls stay on
+    // one stream that costs nothing; when the stream changes, the new one waits for an event recorded
+    // on the old one at that moment.
+    hipStream_t cur_stream = nullptr;
+    hipEvent_t order_ev = nullptr;
     bool launched = false;
-    double* rse_part = nullptr;         // device scratch of difa_head_rse: batch * heads * kRseChunks * 3 sums
-    hipEvent_t rse_last = nullptr;      // after the last difa_head_rse launch (same sharing, same ordering)
-    hipStream_t rse_stream = nullptr;
-    bool rse_launched = false;
     std::vector<difa_work_item_t> recs; // host scratch of the work-list compiler
+    std::vector<int32_t> keys;          // memo keys: kSlots rows of 2 * heads + 2, then one row for the call's own
     Slot slots[kSlots];
+    Staging stagings[kStagings];
+    int next_staging = 0;
     uint64_t clock = 0;
     std::string err;
     bool timing = false;
@@ -77,12 +85,42 @@ std::string hip_msg(const char* what, hipError_t e) {
 
 size_t elem_size(int dtype) { return dtype == DIFA_DTYPE_BF16 ? 2 : 4; }
 
-void free_slot(Slot& s) {
-    if (s.h_buf) (void)hipHostFree(s.h_buf);
-    if (s.d_buf) (void)hipFree(s.d_buf);
-    if (s.uploaded) (void)hipEventDestroy(s.uploaded);
-    if (s.last_use) (void)hipEventDestroy(s.last_use);
-    s = Slot();
+void free_buffers(difa_plan* p) {
+    for (Slot& s : p->slots) {
+        if (s.d_buf) (void)hipFree(s.d_buf);
+        s = Slot();
+    }
+    for (Staging& g : p->stagings) {
+        if (g.h_buf) (void)hipHostFree(g.h_buf);
+        if (g.copied) (void)hipEventDestroy(g.copied);
+        g = Staging();
+    }
+    if (p->part_o) (void)hipFree(p->part_o);
+    if (p->part_ml) (void)hipFree(p->part_ml);
+    if (p->ctl) (void)hipFree(p->ctl);
+    if (p->rse_part) (void)hipFree(p->rse_part);
+    if (p->order_ev) (void)hipEventDestroy(p->order_ev);
+    p->part_o = p->part_ml = nullptr;
+    p->ctl = nullptr;
+    p->rse_part = nullptr;
+    p->order_ev = nullptr;
+}
+
+// Puts what is about to be enqueued on `stream` behind everything this object enqueued before.
+hipError_t order_behind_earlier_calls(difa_plan* p, hipStream_t stream) {
+    if (p->launched && p->cur_stream != stream) {
+        hipError_t e = hipEventRecord(p->order_ev, p->cur_stream);
+        if (e == hipSuccess) e = hipStreamWaitEvent(stream, p->order_ev, 0);
+        if (e != hipSuccess) {
+            // (the earlier stream may have been destroyed by its owner: fall back to the whole device)
+            (void)hipGetLastError();
+            e = hipDeviceSynchronize();
+            if (e != hipSuccess) return e;
+        }
+    }
+    p->cur_stream = stream;
+    p->launched = true;
+    return hipSuccess;
 }
 
 // Switches to the plan's device for the scope of a call and back afterwards.
@@ -202,48 +240,46 @@ extern "C" difa_status_t difa_plan_create(const difa_plan_desc_t* desc, difa_pla
     p->buf_bytes = p->heads_bytes + ((size_t)p->n_wg + 1) * sizeof(int32_t) + 64 +
                    ((size_t)cap + 2 * (size_t)p->n_wg) * sizeof(difa_segment_t) + 64 +
                    2 * (size_t)p->n_wg * sizeof(difa_merge_item_t) + 64 + (size_t)cap * sizeof(difa_work_item_t);
-    p->recs.resize((size_t)cap);
+    try {
+        p->recs.resize((size_t)cap);
+        p->keys.assign((size_t)(kSlots + 1) * (2 * (size_t)desc->heads + 2), 0);
+    } catch (const std::bad_alloc&) {
+        delete p;
+        return fail(nullptr, DIFA_ERR_ALLOC, "out of host memory");
+    }
 
     DeviceGuard guard;
     e = guard.enter(desc->device);
     if (e != hipSuccess) { delete p; return fail(nullptr, DIFA_ERR_HIP, hip_msg("hipSetDevice", e)); }
+    const char* what = "hipGetSymbolAddress(static scratch)";
     e = difa::static_scratch_init(desc->device);   // device address of the file-scope scratch, once per device
-    if (e != hipSuccess) { delete p; return fail(nullptr, DIFA_ERR_HIP, hip_msg("hipGetSymbolAddress(static scratch)", e)); }
-    if (desc->dtype == DIFA_DTYPE_BF16) {
+    if (e == hipSuccess && desc->dtype == DIFA_DTYPE_BF16) {
+        what = "allocating the scratch for cut records";
         const size_t slots = 2 * (size_t)p->n_wg;
         e = hipMalloc((void**)&p->part_o, slots * (size_t)p->bm * desc->head_dim * sizeof(float));
         if (e == hipSuccess) e = hipMalloc((void**)&p->part_ml, slots * (size_t)p->bm * 2 * sizeof(float));
-        if (e == hipSuccess) e = hipEventCreateWithFlags(&p->last_launch, hipEventDisableTiming);
-        if (e != hipSuccess) {
-            if (p->part_o) (void)hipFree(p->part_o);
-            if (p->part_ml) (void)hipFree(p->part_ml);
-            delete p;
-            return fail(nullptr, e == hipErrorOutOfMemory ? DIFA_ERR_ALLOC : DIFA_ERR_HIP,
-                        hip_msg("allocating the scratch for cut records", e));
+        const size_t ctl_bytes = slots * sizeof(int32_t);
+        if (e == hipSuccess) e = hipMalloc((void**)&p->ctl, ctl_bytes);
+        if (e == hipSuccess) e = hipMemset(p->ctl, 0, ctl_bytes);      // (synchronous; the kernels leave them at zero)
+    }
+    if (e == hipSuccess) {
+        what = "allocating work-list buffers";
+        e = hipEventCreateWithFlags(&p->order_ev, hipEventDisableTiming);
+        for (int s = 0; s < kSlots && e == hipSuccess; ++s) e = hipMalloc(&p->slots[s].d_buf, p->buf_bytes);
+        for (int s = 0; s < kStagings && e == hipSuccess; ++s) {
+            e = hipHostMalloc(&p->stagings[s].h_buf, p->buf_bytes, hipHostMallocDefault);
+            if (e == hipSuccess) e = hipEventCreateWithFlags(&p->stagings[s].copied, hipEventDisableTiming);
         }
     }
-    for (int s = 0; s < kSlots; ++s) {
-        Slot& sl = p->slots[s];
-        e = hipHostMalloc(&sl.h_buf, p->buf_bytes, hipHostMallocDefault);
-        if (e == hipSuccess) e = hipMalloc(&sl.d_buf, p->buf_bytes);
-        if (e == hipSuccess) e = hipEventCreateWithFlags(&sl.uploaded, hipEventDisableTiming);
-        if (e == hipSuccess) e = hipEventCreateWithFlags(&sl.last_use, hipEventDisableTiming);
-        if (e != hipSuccess) {
-            for (int t = 0; t <= s; ++t) free_slot(p->slots[t]);
-            if (p->part_o) (void)hipFree(p->part_o);
-            if (p->part_ml) (void)hipFree(p->part_ml);
-            if (p->last_launch) (void)hipEventDestroy(p->last_launch);
-            delete p;
-            return fail(nullptr, e == hipErrorOutOfMemory ? DIFA_ERR_ALLOC : DIFA_ERR_HIP,
-                        hip_msg("allocating work-list buffers", e));
-        }
+    if (e == hipSuccess) {
+        what = "allocating the influence-metric scratch";
+        e = hipMalloc((void**)&p->rse_part, (size_t)desc->batch * desc->heads * difa::kRseChunks * 3 * sizeof(double));
     }
-    e = hipMalloc((void**)&p->rse_part, (size_t)desc->batch * desc->heads * difa::kRseChunks * 3 * sizeof(double));
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&p->rse_last, hipEventDisableTiming);
     if (e != hipSuccess) {
         const difa_status_t st = e == hipErrorOutOfMemory ? DIFA_ERR_ALLOC : DIFA_ERR_HIP;
-        const std::string msg = hip_msg("allocating the influence-metric scratch", e);
-        (void)difa_plan_destroy(p);
+        const std::string msg = hip_msg(what, e);
+        free_buffers(p);
+        delete p;
         return fail(nullptr, st, msg);
     }
     *plan_out = p;
@@ -255,18 +291,13 @@ extern "C" difa_status_t difa_plan_destroy(difa_plan_t* p) {
     DeviceGuard guard;
     (void)guard.enter(p->desc.device);
     (void)timing_flush(p);
-    for (Slot& s : p->slots) {
-        if (s.used && s.last_use) (void)hipEventSynchronize(s.last_use);
-        free_slot(s);
+    // everything the object enqueued is in one order, so the stream of its last call has seen it all
+    if (p->launched && hipStreamSynchronize(p->cur_stream) != hipSuccess) {
+        (void)hipGetLastError();
+        (void)hipDeviceSynchronize();
     }
     for (TimingPair& tp : p->pool) { (void)hipEventDestroy(tp.start); (void)hipEventDestroy(tp.stop); }
-    if (p->launched) (void)hipEventSynchronize(p->last_launch);
-    if (p->part_o) (void)hipFree(p->part_o);
-    if (p->part_ml) (void)hipFree(p->part_ml);
-    if (p->last_launch) (void)hipEventDestroy(p->last_launch);
-    if (p->rse_launched) (void)hipEventSynchronize(p->rse_last);
-    if (p->rse_part) (void)hipFree(p->rse_part);
-    if (p->rse_last) (void)hipEventDestroy(p->rse_last);
+    free_buffers(p);
     delete p;
     return DIFA_OK;
 }
@@ -345,8 +376,12 @@ difa_status_t joint_attention_impl(difa_plan_t* p, const void* q, const void* k,
     hipError_t e = guard.enter(p->desc.device);
     if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("hipSetDevice", e));
 
+    e = order_behind_earlier_calls(p, stream);
+    if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("ordering the call behind earlier ones", e));
+
     // ---- memo lookup: key = effective per-head (mode, window) + token counts
-    std::vector<int32_t> key(2 * (size_t)H + 2);
+    const size_t key_len = 2 * (size_t)H + 2;
+    int32_t* key = p->keys.data() + (size_t)kSlots * key_len;
     for (int h = 0; h < H; ++h) {
         key[2 * h] = head_plan[h];
         key[2 * h + 1] = head_plan[h] == DIFA_HEAD_ARROW ? window[h] : 0;
@@ -354,22 +389,31 @@ difa_status_t joint_attention_impl(difa_plan_t* p, const void* q, const void* k,
     key[2 * H] = n_text;
     key[2 * H + 1] = n_img;
     Slot* slot = nullptr;
-    for (Slot& s : p->slots)
-        if (s.valid && s.key == key) { slot = &s; break; }
+    for (int s = 0; s < kSlots; ++s)
+        if (p->slots[s].valid && memcmp(p->keys.data() + (size_t)s * key_len, key, key_len * sizeof(int32_t)) == 0) {
+            slot = &p->slots[s];
+            break;
+        }
     if (!slot) {
-        Slot* lru = &p->slots[0];
-        for (Slot& s : p->slots) {
-            if (!s.valid) { lru = &s; break; }
-            if (s.stamp < lru->stamp) lru = &s;
+        int victim = 0;
+        for (int s = 0; s < kSlots; ++s) {
+            if (!p->slots[s].valid) { victim = s; break; }
+            if (p->slots[s].stamp < p->slots[victim].stamp) victim = s;
         }
-        // The buffers may still be read by launches enqueued earlier.
-        if (lru->used) {
-            e = hipEventSynchronize(lru->last_use);
-            if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("waiting for a work list in use", e));
+        Slot* lru = &p->slots[victim];
+        // The device buffer may still be read by launches enqueued earlier: the copy below goes on `stream`,
+        // behind all of them.  The pinned buffer it is written into on the host may still be the source of a
+        // copy issued kStagings distinct plans ago that the device has not reached yet: only then the host waits.
+        Staging& stg = p->stagings[p->next_staging];
+        if (stg.pending && hipEventQuery(stg.copied) != hipSuccess) {
+            (void)hipGetLastError();
+            e = hipEventSynchronize(stg.copied);
+            if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("waiting for an earlier work-list upload", e));
         }
+        stg.pending = false;
         lru->valid = false;
         int32_t n_items = 0, n_copy = 0, n_segs = 0, n_merges = 0, n_slots = 0;
-        char* hb = (char*)lru->h_buf;
+        char* hb = (char*)stg.h_buf;
         difa_status_t st = difa_worklist_build(B, H, head_plan, window, n_text, n_img, p->bm, p->bn, 1, p->desc.flags,
                                                p->recs.data(), p->item_capacity, &n_items, (int32_t*)hb, &n_copy);
         if (st != DIFA_OK) return fail(p, st, "work-list compilation failed");
@@ -390,22 +434,18 @@ difa_status_t joint_attention_impl(difa_plan_t* p, const void* q, const void* k,
             memcpy(hb + used, p->recs.data(), (size_t)n_items * sizeof(difa_work_item_t));
             used += (size_t)n_items * sizeof(difa_work_item_t);
         }
-        e = hipMemcpyAsync(lru->d_buf, lru->h_buf, used, hipMemcpyHostToDevice, stream);   // only the part in use
-        if (e == hipSuccess) e = hipEventRecord(lru->uploaded, stream);
+        e = hipMemcpyAsync(lru->d_buf, stg.h_buf, used, hipMemcpyHostToDevice, stream);   // only the part in use
+        if (e == hipSuccess) e = hipEventRecord(stg.copied, stream);
+        stg.pending = true;
+        p->next_staging = (p->next_staging + 1) % kStagings;
         if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("uploading the work list", e));
         lru->n_merges = n_merges;
         lru->n_slots = n_slots;
-        lru->key = key;
         lru->n_items = n_items;
         lru->n_copy = n_copy;
-        lru->upload_stream = stream;
+        memcpy(p->keys.data() + (size_t)victim * key_len, key, key_len * sizeof(int32_t));
         lru->valid = true;
-        lru->used = true;  // the upload itself reads h_buf
-        (void)hipEventRecord(lru->last_use, stream);
         slot = lru;
-    } else if (slot->upload_stream != stream) {
-        e = hipStreamWaitEvent(stream, slot->uploaded, 0);
-        if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("hipStreamWaitEvent", e));
     }
     slot->stamp = ++p->clock;
 
@@ -416,9 +456,11 @@ difa_status_t joint_attention_impl(difa_plan_t* p, const void* q, const void* k,
     } else {
         sh = D; sn = (int64_t)H * D; sb = (int64_t)N * H * D;
     }
+    const bool fast = p->desc.dtype == DIFA_DTYPE_BF16;
+    const bool copies = slot->n_copy > 0 && cache != out;   // cached heads (Sec. 3.2): out[b, h] = cache[b, h]
 
-    // ---- cached heads: coalesced copy (Alg. 1, O[idx] = O_cache[idx]); nothing else runs for them
-    if (slot->n_copy > 0 && cache != out) {
+    // ---- fp32 debug path: cached heads by a copy kernel of their own
+    if (!fast && copies) {
         difa::CopyArgs c{};
         c.src = cache;
         c.dst = out;
@@ -434,8 +476,8 @@ difa_status_t joint_attention_impl(difa_plan_t* p, const void* q, const void* k,
         if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("cache-copy launch", e));
     }
 
-    // ---- computed heads
-    if (slot->n_items > 0) {
+    // ---- one launch: the computed heads and, on the bf16 path, the cached heads as well
+    if (slot->n_items > 0 || (fast && copies)) {
         const char* db = (const char*)slot->d_buf;
         difa::AttnArgs a{};
         a.q = q; a.k = k; a.v = v; a.out = out;
@@ -445,7 +487,7 @@ difa_status_t joint_attention_impl(difa_plan_t* p, const void* q, const void* k,
         a.merges = (const difa_merge_item_t*)(db + slot->merges_off);
         a.part_o = p->part_o;
         a.part_ml = p->part_ml;
-        if (static_scratch && p->desc.dtype == DIFA_DTYPE_BF16 && slot->n_slots > 0) {
+        if (static_scratch && fast && slot->n_slots > 0) {
             // [n_slots][bm][head_dim] accumulators, then [n_slots][bm][2] row references and sums
             size_t cap = 0;
             float* base = difa::static_scratch(p->desc.device, &cap);
@@ -468,29 +510,32 @@ difa_status_t joint_attention_impl(difa_plan_t* p, const void* q, const void* k,
         a.n_kv_tiles = (N + p->bn - 1) / p->bn;
         a.tile_rot = image_first && n_text > 0 && n_img > 0 ? n_img / p->bn : 0;   // as difa_worklist_build numbers the tiles
         a.scale = p->scale;
-        const bool fast = p->desc.dtype == DIFA_DTYPE_BF16;
-        // the scratch for cut records is shared by all calls on this object: order them across streams
-        if (fast && p->launched && p->last_stream != stream) {
-            e = hipStreamWaitEvent(stream, p->last_launch, 0);
-            if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("hipStreamWaitEvent", e));
+        if (fast) {
+            a.tickets = p->ctl;
+            if (copies) {
+                const int vec_per_row = (int)(D * es / 16);                 // 8 or 16: a power of two
+                int shift = 0;
+                while ((1 << shift) < vec_per_row) ++shift;
+                a.copy_src = cache;
+                a.copy_heads = (const int32_t*)slot->d_buf;
+                a.copy_stride_b = sb * (int64_t)es; a.copy_stride_h = sh * (int64_t)es; a.copy_stride_n = sn * (int64_t)es;
+                a.n_copy = slot->n_copy;
+                a.copy_vec_shift = shift;
+                a.copy_head_vecs = N << shift;
+                a.copy_chunks_per_head = (a.copy_head_vecs + difa::kCopyVecs - 1) / difa::kCopyVecs;
+                const int64_t chunks = (int64_t)B * slot->n_copy * a.copy_chunks_per_head;
+                if (chunks > INT32_MAX) return fail(p, DIFA_ERR_UNSUPPORTED, "too many cached-head chunks");
+                a.copy_chunks = (int32_t)chunks;
+            }
         }
         TimingPair tp{};
         if (p->timing && (e = timing_begin(p, stream, 0, &tp)) != hipSuccess)
             return fail(p, DIFA_ERR_HIP, hip_msg("hipEventRecord", e));
-        e = fast ? difa::launch_attn_bf16(a, D, p->n_wg, slot->n_merges, stream)
+        e = fast ? difa::launch_attn_bf16(a, D, p->n_wg, stream)
                  : difa::launch_attn_f32(a, D, slot->n_items, stream);
         if (p->timing) { (void)hipEventRecord(tp.stop, stream); p->pending.push_back(tp); }
         if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("attention launch", e));
-        if (fast) {
-            e = hipEventRecord(p->last_launch, stream);
-            if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("hipEventRecord", e));
-            p->last_stream = stream;
-            p->launched = true;
-        }
     }
-    e = hipEventRecord(slot->last_use, stream);
-    if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("hipEventRecord", e));
-    slot->used = true;
     if (p->timing && p->pending.size() > 512) (void)timing_flush(p);
     return DIFA_OK;
 }
@@ -538,20 +583,14 @@ extern "C" difa_status_t difa_head_rse(difa_plan_t* p, const void* y_m, const vo
     if (p->desc.layout == DIFA_LAYOUT_BHND) { a.stride_n = D; a.stride_h = N * D; a.stride_b = H * N * D; }
     else { a.stride_h = D; a.stride_n = H * D; a.stride_b = N * H * D; }
     a.batch = p->desc.batch; a.heads = p->desc.heads; a.n_tokens = n_tokens; a.head_dim = p->desc.head_dim;
-    // the partial sums live in one scratch per plan object: order the calls across streams
-    if (p->rse_launched && p->rse_stream != stream) {
-        e = hipStreamWaitEvent(stream, p->rse_last, 0);
-        if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("hipStreamWaitEvent", e));
-    }
+    // the partial sums live in one scratch per plan object
+    e = order_behind_earlier_calls(p, stream);
+    if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("ordering the call behind earlier ones", e));
     TimingPair tp{};
     if (p->timing && (e = timing_begin(p, stream, 2, &tp)) != hipSuccess)
         return fail(p, DIFA_ERR_HIP, hip_msg("hipEventRecord", e));
     e = difa::launch_head_rse(a, p->desc.dtype, stream);
     if (p->timing) { (void)hipEventRecord(tp.stop, stream); p->pending.push_back(tp); }
     if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("influence-metric launch", e));
-    e = hipEventRecord(p->rse_last, stream);
-    if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("hipEventRecord", e));
-    p->rse_stream = stream;
-    p->rse_launched = true;
     return DIFA_OK;
 }

@@ -9,6 +9,7 @@ namespace difa {
 
 constexpr int kBM = 256;  // query rows per workgroup (8 wavefronts x 32 rows)
 constexpr int kBN = 64;   // keys per K/V tile
+constexpr int kCopyVecs = 8192;  // 16-byte vectors per chunk of the cached-head copy (128 KiB)
 
 // Arguments common to the attention kernels.  Strides are in elements.
 struct AttnArgs {
@@ -22,6 +23,16 @@ struct AttnArgs {
     const difa_merge_item_t* merges;  // device: records cut into pieces
     float* part_o;                  // device scratch: [slot][kBM][head_dim] unnormalised accumulators
     float* part_ml;                 // device scratch: [slot][kBM][2] row reference (log2 domain), row sum
+    int32_t* tickets;               // device, one per cut record, zero between launches: pieces finished so far
+    // cached heads (bf16 kernel): out[b, h] = copy_src[b, h] for the heads listed in copy_heads
+    const void* copy_src;
+    const int32_t* copy_heads;      // device, n_copy entries
+    int64_t copy_stride_b, copy_stride_h, copy_stride_n;   // in bytes
+    int32_t n_copy;
+    int32_t copy_chunks;            // batch * n_copy * copy_chunks_per_head; 0: nothing to copy
+    int32_t copy_chunks_per_head;
+    int32_t copy_head_vecs;         // 16-byte vectors per (batch entry, head): n_tokens << copy_vec_shift
+    int32_t copy_vec_shift;         // log2(16-byte vectors per token row)
     int64_t stride_b, stride_h, stride_n;
     int32_t heads, n_tokens, n_text;
     int32_t text_begin;  // first text token: 0, or n_img when the image tokens come first
@@ -50,7 +61,7 @@ struct RseArgs {
 };
 
 // Launchers (defined in difa_kernels.hip and difa_rse.hip).  All enqueue on `stream` and return the launch status.
-hipError_t launch_attn_bf16(const AttnArgs& a, int head_dim, int n_wg, int n_merges, hipStream_t stream);
+hipError_t launch_attn_bf16(const AttnArgs& a, int head_dim, int n_wg, hipStream_t stream);
 hipError_t launch_attn_f32(const AttnArgs& a, int head_dim, int n_items, hipStream_t stream);
 hipError_t launch_cache_copy(const CopyArgs& a, hipStream_t stream);
 hipError_t launch_head_rse(const RseArgs& a, int dtype, hipStream_t stream);

@@ -1,7 +1,9 @@
 // gfx950 kernels of the head-wise joint-attention operator (Sec. 3.3 of the paper):
-//   attn_bf16_kernel  -- full / arrow heads, bf16 MFMA with fp32 accumulation
-//   attn_f32_kernel   -- the same result in plain fp32 arithmetic (slow debug path)
-//   cache_copy_kernel -- cached heads: out[b,h] = cache[b,h] (Alg. 1, last statement)
+//   attn_bf16_kernel  -- the whole layer in one launch: full / arrow heads with bf16 MFMA and fp32
+//                        accumulation, then the cached heads, out[b,h] = cache[b,h] (the cache fill that
+//                        ends Alg. 1), copied by whichever workgroups have finished their attention work
+//   attn_f32_kernel   -- full / arrow heads in plain fp32 arithmetic (slow debug path)
+//   cache_copy_kernel -- cached heads of the debug path
 #include <mutex>
 #include <type_traits>
 
@@ -91,6 +93,10 @@ __device__ __forceinline__ void mfma_s_acc(floatx16& d, const bf16x8& k, const b
 }
 __device__ __forceinline__ void mfma_results_visible() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
 
+// Cache-policy operand of the buffer load/store builtins: device scope ("sc1").
+constexpr int kDeviceCoherent = 16;
+typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
+
 struct RowState {
     float m;       // reference maximum (log2 domain) the weights are expressed against
     float l;       // running sum of this lane's half of the keys
@@ -122,8 +128,18 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
     auto vswz = [](int r) { return CPR == 16 ? 4 * (r & 3) : 2 * (r & 3); };
     __shared__ __attribute__((aligned(16))) __bf16 Ksm[NS * TILE];
     __shared__ __attribute__((aligned(16))) __bf16 Vsm[NS * TILE];
+    __shared__ int ctl_sm[1];                // a ticket, handed from thread 0 to the workgroup
+    // The arguments that only the rare paths use (merging a cut record, the cached-head copy) are read
+    // from the kernel-argument block where they are needed: named through `a` they would be fetched at
+    // kernel entry and held in scalar registers for the whole key loop, which has none to spare.
+    auto cold_args = []() __attribute__((always_inline)) {
+        unsigned long long kp = (unsigned long long)__builtin_amdgcn_kernarg_segment_ptr();
+        asm volatile("" : "+s"(kp));
+        return (const AttnArgs*)kp;
+    };
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int tid = threadIdx.x, wave = tid >> 6;
+    int l32, half;                                          // lane % 32, lane / 32 (set by lane_offsets below)
     const int N = a.n_tokens, n_text = a.n_text;
     // text tokens are [text_begin, text_begin + n_text), image tokens [img0, img1) (the text block sits
     // before or after the image block); a record's key-tile position u is tile (u + tile_rot) % n_kv_tiles
@@ -132,19 +148,9 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
     auto tile_at = [&](int u) { const int t = u + a.tile_rot; return t >= a.n_kv_tiles ? t - a.n_kv_tiles : t; };
     const float c = a.scale * 1.44269504088896340736f;      // scores are kept in the log2 domain
 
-    // ---- per-lane LDS offsets (elements, within one stage)
+    // ---- per-lane offsets: LDS operand reads (elements, within one stage) and the lane's place in a tile load
     int koff[KS];                                           // A operand of S^T: row l32, chunk 2*ks+half
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) koff[ks] = l32 * D + 8 * ((2 * ks + half) ^ kswz(l32));
     int voff[DB];                                           // transpose read: row 4*half + s/4, 4 features
-    {
-        const int blk = lane >> 4, s16 = lane & 15;
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-            const int chunk = 4 * db + 2 * (blk & 1) + ((s16 & 3) >> 1);
-            voff[db] = (4 * half + (s16 >> 2)) * D + 8 * (chunk ^ vswz(s16 >> 2)) + 4 * (s16 & 1);
-        }
-    }
 
     // ---- global -> LDS: K/V tiles are written into the ring by the load itself
     // (buffer_load_dwordx4 ... lds: lane l of a wavefront deposits its 16 bytes at M0 + 16*l), so a
@@ -160,12 +166,31 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
     uintx4 krsrc, vrsrc;                                    // descriptors of the head whose tiles are being loaded
     const unsigned wave_u = __builtin_amdgcn_readfirstlane(wave);
     unsigned gk[NDMA], gv[NDMA];                            // per-lane byte offsets inside a tile
+    // These sixteen-odd registers are derived from the lane number again at the start of every segment,
+    // through a copy the compiler cannot see through.  Held for the whole kernel instead, they would be
+    // live across the rare, register-hungry paths between segments (merging a cut record, the cached-head
+    // copy), and the register allocator would answer by parking some of them in accumulation registers
+    // and fetching them back inside the key loop.
+    auto lane_offsets = [&]() __attribute__((always_inline)) {
+        int lane = tid & 63;
+        asm volatile("" : "+v"(lane));
+        l32 = lane & 31;
+        half = lane >> 5;
 #pragma unroll
-    for (int u = 0; u < NDMA; ++u) {
-        const int r = (wave * NDMA + u) * RPI + lane / CPR, pc = lane % CPR;   // tile row, chunk slot in LDS
-        gk[u] = (unsigned)(r * (int)a.stride_n + 8 * (pc ^ kswz(r))) * 2u;
-        gv[u] = (unsigned)(r * (int)a.stride_n + 8 * (pc ^ vswz(r))) * 2u;
-    }
+        for (int ks = 0; ks < KS; ++ks) koff[ks] = l32 * D + 8 * ((2 * ks + half) ^ kswz(l32));
+        const int blk = lane >> 4, s16 = lane & 15;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            const int chunk = 4 * db + 2 * (blk & 1) + ((s16 & 3) >> 1);
+            voff[db] = (4 * half + (s16 >> 2)) * D + 8 * (chunk ^ vswz(s16 >> 2)) + 4 * (s16 & 1);
+        }
+#pragma unroll
+        for (int u = 0; u < NDMA; ++u) {
+            const int r = (wave * NDMA + u) * RPI + lane / CPR, pc = lane % CPR;   // tile row, chunk slot in LDS
+            gk[u] = (unsigned)(r * (int)a.stride_n + 8 * (pc ^ kswz(r))) * 2u;
+            gv[u] = (unsigned)(r * (int)a.stride_n + 8 * (pc ^ vswz(r))) * 2u;
+        }
+    };
     const unsigned tile_bytes = (unsigned)(kBN * (int)a.stride_n) * 2u;
     const unsigned k_lds = (unsigned)(unsigned long long)(__attribute__((address_space(3))) __bf16*)Ksm;
     const unsigned v_lds = (unsigned)(unsigned long long)(__attribute__((address_space(3))) __bf16*)Vsm;
@@ -191,7 +216,7 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
     // Requested ahead of time: for the first segment at once, for every other one by its predecessor,
     // between the end of its own key loop and its epilogue.
     bf16x8 qf[QB][KS];
-    auto first_loads = [&](const difa_segment_t& sg, int sb) __attribute__((always_inline)) {
+    auto first_tiles = [&](const difa_segment_t& sg, int sb) __attribute__((always_inline)) {
         const int b = sg.bh / a.heads, h = sg.bh - b * a.heads;
         const int64_t base = (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
         const unsigned long long ka = (unsigned long long)((const __bf16*)a.k + base);
@@ -211,6 +236,11 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
                 if (t < 2) dma_part(1, u, tb, v_lds + st);
             }
         }
+    };
+    constexpr int kFirstTileLoads = 5 * NDMA;               // load instructions first_tiles issues
+    auto query_rows = [&](const difa_segment_t& sg) __attribute__((always_inline)) {
+        const int b = sg.bh / a.heads, h = sg.bh - b * a.heads;
+        const int64_t base = (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
         const __bf16* qg = (const __bf16*)a.q + base;
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
@@ -222,16 +252,58 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
             for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = *(const bf16x8*)(qrow + 16 * ks);
         }
     };
+    auto first_loads = [&](const difa_segment_t& sg, int sb) __attribute__((always_inline)) {
+        first_tiles(sg, sb);
+        query_rows(sg);
+    };
 
     // Persistent workgroup: one per compute unit, walking the segments the host scheduled for it.
     // The record of the following segment is fetched while the current one runs.
     const int seg_end = __builtin_amdgcn_readfirstlane(a.wg_begin[blockIdx.x + 1]);
     const int seg_first = __builtin_amdgcn_readfirstlane(a.wg_begin[blockIdx.x]);
-    if (seg_first >= seg_end) return;
-    difa_segment_t seg_next = a.segs[seg_first];
+    // ---- cached heads (Sec. 3.2; the cache fill that ends Alg. 1): out[b, h] = cache[b, h], bit for bit.
+    // HBM-bound work that needs no matrix core.  It is cut into chunks of kCopyVecs 16-byte vectors of one
+    // (batch entry, cached head); workgroup p takes chunks p, p + gridDim.x, ... and moves one after each of
+    // its attention segments, when it waits for the next segment's first tiles anyway, so the copy is
+    // spread over the launch and runs in the shadow of the other workgroups' arithmetic.
+    auto copy_chunk = [&](int chunk) __attribute__((always_inline)) {
+        constexpr int PER = kCopyVecs / (NW * 64);          // vectors per thread and chunk, all in flight together
+        const AttnArgs* ca = cold_args();
+        const int per_head = ca->copy_chunks_per_head, n_copy = ca->n_copy, shift = ca->copy_vec_shift;
+        const int head_vecs = ca->copy_head_vecs;
+        const unsigned row_bytes = (unsigned)ca->copy_stride_n;     // (a head spans less than 2 GiB)
+        const int hh = chunk / per_head, cc = chunk - hh * per_head;
+        const int bb = hh / n_copy, head = ca->copy_heads[hh - bb * n_copy];
+        const int64_t base = (int64_t)bb * ca->copy_stride_b + (int64_t)head * ca->copy_stride_h;
+        const char* __restrict__ src = (const char*)ca->copy_src + base;
+        char* __restrict__ dst = (char*)ca->out + base;
+        uintx4 val[PER];
+        unsigned off[PER];
+        bool live[PER];
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            int vi = cc * kCopyVecs + u * (NW * 64) + tid;                // vector inside the head
+            live[u] = vi < head_vecs;
+            vi = live[u] ? vi : head_vecs - 1;                            // past the end: reread the last one, store nothing
+            off[u] = (unsigned)(vi >> shift) * row_bytes + (unsigned)(vi & ((1 << shift) - 1)) * 16u;
+        }
+#pragma unroll
+        for (int u = 0; u < PER; ++u) val[u] = *(const uintx4*)(src + off[u]);
+#pragma unroll
+        for (int u = 0; u < PER; ++u)
+            if (live[u]) *(uintx4*)(dst + off[u]) = val[u];
+    };
+    int next_chunk = (int)blockIdx.x;
+
+    difa_segment_t seg_next{};
     int sbase = 0;                                          // ring stage of the current segment's tile 0
-    first_loads(seg_next, sbase);
+    if (seg_first < seg_end) {
+        seg_next = a.segs[seg_first];
+        lane_offsets();
+        first_loads(seg_next, sbase);
+    }
     for (int seg_idx = seg_first; seg_idx < seg_end; ++seg_idx) {
+    lane_offsets();
     // (the record was read with vector loads; moving its fields to scalar registers tells the compiler
     // that everything derived from them is uniform over the wavefront)
     difa_segment_t it;
@@ -247,6 +319,9 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
     it.pos_begin = __builtin_amdgcn_readfirstlane(seg_next.pos_begin);
     it.pos_end = __builtin_amdgcn_readfirstlane(seg_next.pos_end);
     it.part_slot = __builtin_amdgcn_readfirstlane(seg_next.part_slot);
+    it.merge_idx = __builtin_amdgcn_readfirstlane(seg_next.merge_idx);
+    it.n_parts = __builtin_amdgcn_readfirstlane(seg_next.n_parts);
+    it.first_slot = __builtin_amdgcn_readfirstlane(seg_next.first_slot);
 
     const int b = it.bh / a.heads, h = it.bh - b * a.heads;
     __bf16* __restrict__ og = (__bf16*)a.out + (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
@@ -605,7 +680,7 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
     dma_wait_all();
     __syncthreads();
     const int sbase_next = (sbase + n_iter) & 3;            // keeps clear of the stage the last P V still reads
-    if (seg_idx + 1 < seg_end) first_loads(seg_next, sbase_next);
+    if (seg_idx + 1 < seg_end && it.part_slot < 0) first_loads(seg_next, sbase_next);   // (a piece: after its slot stores)
     // P V of the very last block (its first operands are already in flight)
     {
         const __bf16* vst = vptr(v_cur, 1);
@@ -619,7 +694,97 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
     }
 
     // ---- epilogue: O^T register r of block db is feature d = 32*db + 8*(r/4) + 4*half + r%4
-    if (it.part_slot < 0) {
+    float l_fin[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) l_fin[qb] = halves_sum(rs[qb].l);
+    bool writes_rows = it.part_slot < 0;
+    if (it.part_slot >= 0) {
+        // A piece of a cut record.  Its unnormalised fp32 accumulators, row reference (log2 domain) and row
+        // sum go to the piece's scratch slot; then it takes a ticket of the record.  The piece that draws
+        // the last ticket folds the other pieces' slots into its own accumulators,
+        //     O = sum_p O_p 2^(m_p - M),  l = sum_p l_p 2^(m_p - M),  M = max_p m_p,
+        // in the register layout it already holds them in, writes the record's rows like a whole record
+        // and puts the ticket counter back to zero for the next launch.
+        // The slot stores and loads are device-coherent ("sc1": written through and read around a stale L2
+        // line): another piece may run on another accelerator die, with an L2 of its own, and ordinary
+        // accesses would need a device-wide release and acquire, i.e. writing back and invalidating a die's
+        // whole L2, the K/V tiles its workgroups share included.
+        const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(a.part_o, 0, 0x7fffffff, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rm = __builtin_amdgcn_make_buffer_rsrc(a.part_ml, 0, 0x7fffffff, 0x00020000);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const int rl = it.part_slot * kBM + wave * RW + 32 * qb + l32;       // row inside the scratch
+            if (i_raw[qb] < N) {
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        floatx4 w4;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) w4[e] = o[db][qb][4 * g + e];
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4, w4), ro,
+                                                               (rl * D + 32 * db + 8 * g + 4 * half) * 4, 0, kDeviceCoherent);
+                    }
+                if (half == 0) {
+                    floatx2 ml;
+                    ml[0] = rs[qb].m;
+                    ml[1] = l_fin[qb];
+                    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(uintx2, ml), rm, rl * 8, 0, kDeviceCoherent);
+                }
+            }
+        }
+        // The slot has to be written before the ticket is taken.  The next segment's query rows and first
+        // tiles are requested behind the slot stores, and the tiles are not waited for: memory operations
+        // complete in the order they were issued, so "all but the youngest kFirstTileLoads" covers the
+        // stores.  (The empty statements keep the compiler from moving a memory operation across them, so
+        // that no store is issued among the tile loads; anything it adds there only makes the wait stricter.)
+        if (seg_idx + 1 < seg_end) {
+            asm volatile("" ::: "memory");
+            query_rows(seg_next);
+            asm volatile("" ::: "memory");
+            first_tiles(seg_next, sbase_next);
+            asm volatile("s_waitcnt vmcnt(%0)" :: "n"(kFirstTileLoads) : "memory");
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+        __syncthreads();                                     // ... by every wavefront
+        if (tid == 0) ctl_sm[0] = atomicAdd(cold_args()->tickets + it.merge_idx, 1);
+        __syncthreads();
+        if (ctl_sm[0] == it.n_parts - 1) {
+#pragma unroll 1
+            for (int p = 0; p < it.n_parts; ++p) {
+                const int slot = it.first_slot + p;
+                if (slot == it.part_slot) continue;
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    const int rl = slot * kBM + wave * RW + 32 * qb + l32;
+                    // (whole vectors are reinterpreted: a bit_cast applied to one vector element reads element 0)
+                    const floatx2 ml = __builtin_bit_cast(floatx2, __builtin_amdgcn_raw_buffer_load_b64(rm, rl * 8, 0, kDeviceCoherent));
+                    floatx4 x[DB][4];
+#pragma unroll
+                    for (int db = 0; db < DB; ++db)
+#pragma unroll
+                        for (int g = 0; g < 4; ++g)
+                            x[db][g] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(
+                                ro, (rl * D + 32 * db + 8 * g + 4 * half) * 4, 0, kDeviceCoherent));
+                    const float m_new = fmaxf(rs[qb].m, ml[0]);
+                    const float w_mine = __builtin_amdgcn_exp2f(rs[qb].m - m_new), w_other = __builtin_amdgcn_exp2f(ml[0] - m_new);
+                    rs[qb].m = m_new;
+                    l_fin[qb] = fmaf(ml[1], w_other, l_fin[qb] * w_mine);
+#pragma unroll
+                    for (int db = 0; db < DB; ++db)
+#pragma unroll
+                        for (int g = 0; g < 4; ++g)
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                o[db][qb][4 * g + e] = fmaf(x[db][g][e], w_other, o[db][qb][4 * g + e] * w_mine);
+                }
+            }
+            if (tid == 0) atomicExch(cold_args()->tickets + it.merge_idx, 0);
+            writes_rows = true;
+        }
+    }
+    if (writes_rows) {
         // A lane holds features 8g + 4*half + (0..3) of its row for g = 0..3 in each block db.  The two
         // halves of the wavefront exchange one quad per pair (g, g+1), after which the lower half holds
         // features 8g..8g+7 and the upper half 8(g+1)..8(g+1)+7: 16-byte stores, half as many of them (with
@@ -627,8 +792,7 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
         // can track would stall the wavefront until loads return).
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-            const float l_tot = halves_sum(rs[qb].l);
-            const float inv = 1.0f / l_tot;
+            const float inv = 1.0f / l_fin[qb];
             __bf16* orow = og + (int64_t)(i_raw[qb] < N ? i_raw[qb] : N - 1) * a.stride_n;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
@@ -657,73 +821,18 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
                     if (i_raw[qb] < N) *(uintx4*)(orow + 32 * db + 16 * gp + 8 * half) = q4;
                 }
         }
-    } else {
-        // a piece of a record: the unnormalised fp32 accumulators, the row reference (log2 domain)
-        // and the row sum go to the piece's scratch slot; merge_parts_kernel combines the pieces
-        float* po = a.part_o + (int64_t)it.part_slot * (kBM * D);
-        float* pml = a.part_ml + (int64_t)it.part_slot * (kBM * 2);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            const float l_tot = halves_sum(rs[qb].l);
-            const int rl = wave * RW + 32 * qb + l32;        // row inside the query tile
-            if (i_raw[qb] < N) {
-#pragma unroll
-                for (int db = 0; db < DB; ++db)
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        floatx4 w4;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) w4[e] = o[db][qb][4 * g + e];
-                        *(floatx4*)(po + rl * D + 32 * db + 8 * g + 4 * half) = w4;
-                    }
-                if (half == 0) {
-                    floatx2 ml;
-                    ml[0] = rs[qb].m;
-                    ml[1] = l_tot;
-                    *(floatx2*)(pml + rl * 2) = ml;
-                }
-            }
-        }
     }
     sbase = sbase_next;
+    // one chunk of the cached-head copy, while the next segment's first tiles are on their way
+    if (next_chunk < cold_args()->copy_chunks) {
+        copy_chunk(next_chunk);
+        next_chunk += (int)gridDim.x;
     }
-}
-
-// Rows of a record that was cut into pieces: out = sum_p O_p 2^(m_p - M) / sum_p l_p 2^(m_p - M),
-// M = max_p m_p.  kMergeSplit workgroups per record, one thread per (row, 8-feature chunk): the few
-// records that are cut are spread over the whole chip, and the reads of a row are 16-byte vectors.
-constexpr int kMergeSplit = 8;
-template <int D>
-__global__ __launch_bounds__(256) void merge_parts_kernel(AttnArgs a) {
-    const difa_merge_item_t mi = a.merges[blockIdx.x / kMergeSplit];
-    const int b = mi.bh / a.heads, h = mi.bh - b * a.heads;
-    __bf16* og = (__bf16*)a.out + (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
-    constexpr int CH = D / 8;
-    constexpr int ROWS = kBM / kMergeSplit;
-    const int row_base = (blockIdx.x % kMergeSplit) * ROWS;
-    for (int e = threadIdx.x; e < ROWS * CH; e += 256) {
-        const int rl = row_base + e / CH, ch = e % CH;
-        const int i = mi.q_tile * kBM + rl;
-        if (i >= a.n_tokens) continue;
-        float M = -INFINITY;
-        for (int p = 0; p < mi.n_parts; ++p)
-            M = fmaxf(M, a.part_ml[((int64_t)(mi.first_slot + p) * kBM + rl) * 2]);
-        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, l = 0.f;
-        for (int p = 0; p < mi.n_parts; ++p) {
-            const int64_t slot = mi.first_slot + p;
-            const floatx2 ml = *(const floatx2*)(a.part_ml + (slot * kBM + rl) * 2);
-            const float w = __builtin_amdgcn_exp2f(ml[0] - M);
-            l = fmaf(ml[1], w, l);
-            const float* src = a.part_o + (slot * kBM + rl) * D + 8 * ch;
-            const floatx4 x0 = *(const floatx4*)src, x1 = *(const floatx4*)(src + 4);
-#pragma unroll
-            for (int t = 0; t < 4; ++t) { acc[t] = fmaf(x0[t], w, acc[t]); acc[4 + t] = fmaf(x1[t], w, acc[4 + t]); }
-        }
-        const float inv = 1.0f / l;
-        bf16x8 w8;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) w8[t] = (__bf16)(acc[t] * inv);
-        *(bf16x8*)(og + (int64_t)i * a.stride_n + 8 * ch) = w8;
+    }
+    // whatever is left of this workgroup's share of the copy (all of it in a layer with every head cached)
+    {
+        const int copy_chunks = cold_args()->copy_chunks;
+        for (; next_chunk < copy_chunks; next_chunk += (int)gridDim.x) copy_chunk(next_chunk);
     }
 }
 
@@ -768,17 +877,14 @@ float* static_scratch(int device, size_t* bytes) {
 // lowers its clock by as much as the schedule got tighter.
 constexpr int kRowBlocks = 1;
 
-hipError_t launch_attn_bf16(const AttnArgs& a, int head_dim, int n_wg, int n_merges, hipStream_t stream) {
+hipError_t launch_attn_bf16(const AttnArgs& a, int head_dim, int n_wg, hipStream_t stream) {
     if (n_wg <= 0) return hipSuccess;
-    if (head_dim == 128) {
+    if (head_dim == 128)
         hipLaunchKernelGGL((attn_bf16_kernel<128, kRowBlocks>), dim3(n_wg), dim3(512 / kRowBlocks), 0, stream, a);
-        if (n_merges > 0) hipLaunchKernelGGL(merge_parts_kernel<128>, dim3(n_merges * kMergeSplit), dim3(256), 0, stream, a);
-    } else if (head_dim == 64) {
+    else if (head_dim == 64)
         hipLaunchKernelGGL((attn_bf16_kernel<64, kRowBlocks>), dim3(n_wg), dim3(512 / kRowBlocks), 0, stream, a);
-        if (n_merges > 0) hipLaunchKernelGGL(merge_parts_kernel<64>, dim3(n_merges * kMergeSplit), dim3(256), 0, stream, a);
-    } else {
+    else
         return hipErrorInvalidValue;
-    }
     return hipGetLastError();
 }
 
@@ -889,8 +995,8 @@ hipError_t launch_attn_f32(const AttnArgs& a, int head_dim, int n_items, hipStre
 }
 
 // ------------------------------------------------------------------------------------------
-// Cached heads: a 16-byte-per-lane copy of the head's rows, four vectors in flight per thread.
-// HBM bound: 2 * N * D * elem bytes per (batch entry, cached head).
+// Cached heads of the fp32 debug path: a 16-byte-per-lane copy of the head's rows, four vectors in
+// flight per thread.  HBM bound: 2 * N * D * elem bytes per (batch entry, cached head).
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void cache_copy_kernel(CopyArgs c) {
     const int64_t per_head = (int64_t)c.n_tokens * c.vec_per_row;

@@ -267,6 +267,9 @@ difa_segment_t whole_segment(const difa_work_item_t& r) {
     s.window = r.window;
     s.pos_begin = 0; s.pos_end = r.n_tiles;
     s.part_slot = -1;
+    s.merge_idx = -1;
+    s.n_parts = 1;
+    s.first_slot = -1;
     return s;
 }
 
@@ -281,7 +284,12 @@ struct DiePlan {
 void finish_record(DiePlan& plan, const difa_work_item_t& r, std::vector<std::pair<int, difa_segment_t>>& pieces) {
     if (pieces.size() > 1) {
         difa_merge_item_t m{r.bh, r.q_tile, plan.n_slots, (int32_t)pieces.size()};
-        for (auto& pc : pieces) pc.second.part_slot = plan.n_slots++;
+        for (auto& pc : pieces) {
+            pc.second.first_slot = m.first_slot;
+            pc.second.part_slot = plan.n_slots++;
+            pc.second.merge_idx = (int32_t)plan.merges.size();
+            pc.second.n_parts = (int32_t)pieces.size();
+        }
         plan.merges.push_back(m);
     }
     for (auto& pc : pieces) plan.lists[(size_t)pc.first].push_back(pc.second);
@@ -290,7 +298,7 @@ void finish_record(DiePlan& plan, const difa_work_item_t& r, std::vector<std::pa
 // Whole records dealt in order to the least loaded workgroup (neighbouring query tiles of a head run side
 // by side and share its K/V tiles in the die's L2); the records that no longer fit under the target are cut
 // into pieces that fill the workgroups up to it.
-DiePlan deal_and_cut(const std::vector<difa_work_item_t>& q, int per_die, int64_t target, int slot_budget) {
+DiePlan deal_and_cut(const std::vector<difa_work_item_t>& q, int per_die, int64_t target, int slot_budget, bool wide_rooms) {
     DiePlan plan;
     plan.lists.resize((size_t)per_die);
     std::vector<int64_t> load((size_t)per_die, 0);
@@ -299,20 +307,29 @@ DiePlan deal_and_cut(const std::vector<difa_work_item_t>& q, int per_die, int64_
     for (const difa_work_item_t& r : q) {
         const int w = least();
         const int64_t c = range_cost(r, 0, r.n_tiles);
-        if (load[(size_t)w] + c <= target) {
+        // wide_rooms: a workgroup stops taking whole records while it still has room for half a record or
+        // more.  The rooms that the pieces fill are then of the order of a record, a cut record has two or
+        // three pieces, and the workgroup that folds them together at the end reads one or two slots, not ten.
+        if (load[(size_t)w] + c + (wide_rooms ? c / 2 : 0) <= target) {
             plan.lists[(size_t)w].push_back(whole_segment(r));
             load[(size_t)w] += c;
         } else {
             pool.push_back(r);
         }
     }
+    // wide_rooms: the pooled records are laid end to end and poured into the workgroups' rooms, one workgroup
+    // filled before the next (the least loaded one) is opened, so a record is cut where a room ends.
+    // Otherwise every piece goes to the workgroup that is the least loaded at that moment.
+    int cur = -1;
+    auto room_of = [&](int w) { return (target - load[(size_t)w] - kSegOverhead) / kUnit; };   // in key tiles
     for (const difa_work_item_t& r : pool) {
         std::vector<std::pair<int, difa_segment_t>> pieces;
         int pos = 0;
         while (pos < r.n_tiles) {
-            const int w = least();
+            if (!wide_rooms || cur < 0 || room_of(cur) < kMinPiece) cur = least();
+            const int w = cur;
             const int remaining = r.n_tiles - pos;
-            const int64_t room = (target - load[(size_t)w] - kSegOverhead) / kUnit;   // in key tiles
+            const int64_t room = room_of(w);
             int take = remaining;
             const bool may_cut = plan.n_slots + (int)pieces.size() + 2 <= slot_budget;
             if (may_cut && room >= kMinPiece && room < remaining) {
@@ -429,7 +446,17 @@ extern "C" difa_status_t difa_schedule_build(const difa_work_item_t* items, int3
         // every workgroup is expected to take one extra piece
         const int64_t target = (die_cost + (int64_t)per_die * kSegOverhead + per_die - 1) / per_die;
         const int budget = slot_capacity - n_slots - 2 * per_die * (n_xcd - 1 - x);   // this die's share of the slots
-        DiePlan dealt = deal_and_cut(q, per_die, target, budget);
+        DiePlan dealt = deal_and_cut(q, per_die, target, budget, false);
+        // Long records on a well filled die would be cut into many short pieces, all of which one workgroup
+        // has to fold together at the very end: deal again with rooms of the order of a record.
+        int most_parts = 0;
+        for (const difa_merge_item_t& m : dealt.merges) most_parts = std::max(most_parts, (int)m.n_parts);
+        if (most_parts > 3) {
+            DiePlan wide = deal_and_cut(q, per_die, target, budget, true);
+            int wide_parts = 0;
+            for (const difa_merge_item_t& m : wide.merges) wide_parts = std::max(wide_parts, (int)m.n_parts);
+            if (wide_parts < most_parts && wide.makespan * 50 <= dealt.makespan * 51) dealt = std::move(wide);
+        }
         // When the records are few and long compared with a workgroup's share (small layers), dealing whole
         // records leaves the workgroups uneven; filling them one after the other is then the better plan.
         const int64_t even = die_cost / per_die;
@@ -439,7 +466,7 @@ extern "C" difa_status_t difa_schedule_build(const difa_work_item_t* items, int3
         }
         for (int w = 0; w < per_die; ++w)
             for (difa_segment_t sg : dealt.lists[(size_t)w]) {
-                if (sg.part_slot >= 0) sg.part_slot += n_slots;
+                if (sg.part_slot >= 0) { sg.part_slot += n_slots; sg.first_slot += n_slots; sg.merge_idx += (int32_t)merge_list.size(); }
                 lists[(size_t)(w * n_xcd + x)].push_back(sg);
             }
         for (difa_merge_item_t m : dealt.merges) {

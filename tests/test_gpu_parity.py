@@ -254,7 +254,8 @@ def test_kernel_timing_hook():
         for _ in range(3):
             B.difa_joint_attention(plan, q, k, v, out, cache, wl.head_plan, wl.n_text, wl.n_img, wl.window)
         attn_ms, copy_ms, launches = B.difa_plan_timing_read(plan)
-        assert launches == 3 and attn_ms > 0 and copy_ms > 0
+        assert launches == 3 and attn_ms > 0
+        assert copy_ms == 0        # the cached head is copied inside the one launch
         assert B.difa_plan_timing_read(plan)[2] == 0
     finally:
         B.difa_plan_destroy(plan)
