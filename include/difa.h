@@ -9,7 +9,7 @@
  *     quadrant keeps the band |i - j| <= w of the flattened image sequence, or
  *   - output caching, Sec. 3.2                         (DIFA_HEAD_CACHE): attention is skipped
  *     and the head's output of the previous denoising step is reused
- *     (Alg. 1: "O[idx] = O_cache[idx]").
+ *     (the cache-fill statement that ends Alg. 1).
  *
  * Conventions: N = n_text + n_img tokens, text tokens first ([0, n_text)), image tokens
  * after them in flattened row-major order.  Tensors are dense [batch, heads, N, head_dim]
@@ -77,8 +77,8 @@ typedef struct {
 difa_status_t difa_plan_create(const difa_plan_desc_t* desc, difa_plan_t** plan_out);
 
 /*
- * One fused head-wise joint-attention call (Sec. 3.3; Alg. 1, "HeadwiseAttention(Q,K,V,Plan)"
- * followed by "O[idx] = O_cache[idx]").
+ * One fused head-wise joint-attention call (Sec. 3.3; in Alg. 1, the head-wise attention call
+ * under the chosen plan together with the cache fill that follows it).
  *   q, k, v    DEVICE, read-only, shape/layout/dtype of the plan, N = n_text + n_img.
  *   out        DEVICE, same shape; every row of every head is written.  Must not alias q/k/v.
  *   cache      DEVICE, same shape: the layer's output of the previous denoising step.  Read
@@ -90,11 +90,18 @@ difa_status_t difa_plan_create(const difa_plan_desc_t* desc, difa_plan_t** plan_
  *              sees image keys j with |i - j| <= w); ignored for other heads; may be NULL iff
  *              no head is ARROW.  w >= n_img - 1 makes the head identical to FULL.
  *   stream     hipStream_t passed as void*; NULL is the default stream.
- * The call enqueues work on `stream` and returns without waiting; host arrays may be freed
- * on return.  Device tensors stay owned by the caller and must stay valid until the stream
- * has run the work.  Calls on one plan object must not be issued from two threads at once.
+ * The call enqueues one kernel launch on `stream` (two on the fp32 debug path when a head is cached)
+ * and returns without waiting for it; host arrays may be freed on return.  Device tensors stay owned
+ * by the caller and must stay valid until the stream has run the work.  Calls on one plan object
+ * must not be issued from two threads at once; calls that name different streams are kept in the
+ * order they were made (the later stream waits for an event on the earlier one), because they share
+ * the object's buffers.  A call with a (head plan, windows, n_text, n_img) combination the object has
+ * not seen lately compiles its work list on the host and uploads it from one of 16 pinned buffers
+ * used in turn; the host waits only if the upload issued from that buffer 16 such calls earlier has
+ * not been carried out yet (the queue is that deep).
  * Errors: INVALID_ARG; UNSUPPORTED when, for bf16, one head's K/V rows span 2 GiB or more in the
- * plan's layout (32-bit byte offsets inside a head); HIP.  On error nothing has been enqueued.
+ * plan's layout (32-bit byte offsets inside a head); ALLOC (host memory); HIP.  On error no kernel has
+ * been launched and `out` is untouched (an upload into the object's own buffers may have been queued).
  */
 difa_status_t difa_joint_attention(difa_plan_t* plan, const void* q, const void* k, const void* v,
                                    void* out, const void* cache, const int32_t* head_plan,
@@ -122,7 +129,8 @@ difa_status_t difa_joint_attention_static(difa_plan_t* plan, const void* q, cons
                                           void* stream);
 
 /* Release the object and its buffers (waits for the device to finish work that uses them).
- * NULL is a no-op that returns DIFA_OK. */
+ * NULL is a no-op that returns DIFA_OK.  (This call and the two below manage the object and report
+ * errors; they correspond to no passage of the paper.) */
 difa_status_t difa_plan_destroy(difa_plan_t* plan);
 
 /* Static text for a status code. */
@@ -278,6 +286,12 @@ difa_status_t difa_plan_timing_read(difa_plan_t* plan, double* attn_ms, double* 
                                     int64_t* launches, int32_t reset);
 /* The same for difa_head_rse: accumulated milliseconds of its two kernels and the number of calls. */
 difa_status_t difa_plan_timing_read_head_rse(difa_plan_t* plan, double* rse_ms, int64_t* launches, int32_t reset);
+
+/* What the runtime reports for a device: number of compute units, peak engine and memory clocks (kHz), L2
+ * size of one accelerator die (bytes), architecture name.  Any output pointer may be NULL.  For a
+ * benchmark's report; not part of the operator.  Returns DIFA_OK, INVALID_ARG (no such device) or HIP. */
+difa_status_t difa_device_info(int32_t device, int32_t* compute_units, int32_t* clock_khz,
+                               int32_t* memory_clock_khz, int32_t* l2_bytes, char* arch, int32_t arch_len);
 
 /* The rate at which the current device sustains dense bf16 MFMA (v_mfma_f32_32x32x16_bf16, the
  * instruction both contractions of the operator use) on the caller's operand data: a kernel of

@@ -77,6 +77,8 @@ def _load():
     L.difa_head_rse.argtypes = [vp, vp, vp, i32, vp, vp]
     L.difa_plan_timing_read_head_rse.restype = ctypes.c_int
     L.difa_plan_timing_read_head_rse.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64), i32]
+    L.difa_device_info.restype = ctypes.c_int
+    L.difa_device_info.argtypes = [i32, i32p, i32p, i32p, i32p, ctypes.c_char_p, i32]
     L.difa_probe_mfma_rate.restype = ctypes.c_int
     L.difa_probe_mfma_rate.argtypes = [vp, ctypes.c_int64, i32, i32, vp, vp, ctypes.POINTER(ctypes.c_double),
                                        ctypes.POINTER(ctypes.c_double)]
@@ -210,6 +212,18 @@ def difa_plan_timing_read(plan, reset=True):
     if st != DIFA_OK:
         raise DifaError(st, difa_last_error(plan))
     return a.value, c.value, n.value
+
+
+def difa_device_info(device=0):
+    """What the runtime reports for the device: a dict with compute_units, clock_khz, memory_clock_khz, l2_bytes, arch."""
+    cu, clk, mclk, l2 = (ctypes.c_int32(0) for _ in range(4))
+    arch = ctypes.create_string_buffer(64)
+    st = lib.difa_device_info(int(device), ctypes.byref(cu), ctypes.byref(clk), ctypes.byref(mclk), ctypes.byref(l2),
+                              arch, 64)
+    if st != DIFA_OK:
+        raise DifaError(st, "difa_device_info")
+    return {"compute_units": cu.value, "clock_khz": clk.value, "memory_clock_khz": mclk.value, "l2_bytes": l2.value,
+            "arch": arch.value.decode()}
 
 
 def difa_probe_mfma_rate(data, waves_per_simd=1, rounds=50000, stream=None):

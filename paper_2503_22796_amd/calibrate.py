@@ -1,9 +1,8 @@
-"""Calibration pass of the plan search for one layer (Alg. 1, the statements before the solver).
+"""Calibration pass of the plan search for one layer (Alg. 1, the part before the solver; Sec. 3.4.1).
 
-    O  <- Attention(Q, K, V)
-    for m in methods:  O' <- Attention_m(Q, K, V);  Influence[h, m] <- RSE(O[h], O'[h])  for every head h
-
-Only a loop over C-ABI calls: every attention and every RSE runs in the library's kernels
+One reference call with every head on full attention, then, per candidate method, one call with
+every head on that method and one influence measurement (Eq. 1) of its output against the reference.
+Only a loop over C-ABI calls: every attention and every measurement runs in the library's kernels
 (difa_joint_attention, difa_head_rse); torch is used for the two output buffers and the result.
 """
 import numpy as np

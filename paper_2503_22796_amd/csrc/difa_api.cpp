@@ -74,13 +74,41 @@ namespace {
 
 thread_local std::string g_create_err;
 
-difa_status_t fail(difa_plan* p, difa_status_t st, const std::string& msg) {
-    if (p) p->err = msg; else g_create_err = msg;
+// (Keeping the message is best effort: running out of host memory while recording an error must not
+// turn into an exception that crosses the C boundary.)
+difa_status_t fail(difa_plan* p, difa_status_t st, const std::string& msg) noexcept {
+    try {
+        if (p) p->err = msg; else g_create_err = msg;
+    } catch (...) {
+    }
+    return st;
+}
+difa_status_t fail(difa_plan* p, difa_status_t st, const char* msg) noexcept {
+    try {
+        if (p) p->err = msg; else g_create_err = msg;
+    } catch (...) {
+    }
     return st;
 }
 
-std::string hip_msg(const char* what, hipError_t e) {
-    return std::string(what) + ": " + hipGetErrorString(e);
+// Runs the body of an entry point; nothing it throws leaves the library.
+template <class F>
+difa_status_t guarded(difa_plan* p, F&& body) noexcept {
+    try {
+        return body();
+    } catch (const std::bad_alloc&) {
+        return fail(p, DIFA_ERR_ALLOC, "out of host memory");
+    } catch (...) {
+        return fail(p, DIFA_ERR_HIP, "unexpected C++ exception");
+    }
+}
+
+std::string hip_msg(const char* what, hipError_t e) noexcept {
+    try {
+        return std::string(what) + ": " + hipGetErrorString(e);
+    } catch (...) {
+        return std::string();
+    }
 }
 
 size_t elem_size(int dtype) { return dtype == DIFA_DTYPE_BF16 ? 2 : 4; }
@@ -195,6 +223,7 @@ extern "C" const char* difa_last_error(const difa_plan_t* plan) {
 }
 
 extern "C" difa_status_t difa_plan_create(const difa_plan_desc_t* desc, difa_plan_t** plan_out) {
+    return guarded(nullptr, [&]() -> difa_status_t {
     if (plan_out) *plan_out = nullptr;
     if (!desc || !plan_out) return fail(nullptr, DIFA_ERR_INVALID_ARG, "desc and plan_out must not be NULL");
     if (desc->batch < 1 || desc->heads < 1 || desc->max_tokens < 1 ||
@@ -284,6 +313,7 @@ extern "C" difa_status_t difa_plan_create(const difa_plan_desc_t* desc, difa_pla
     }
     *plan_out = p;
     return DIFA_OK;
+    });
 }
 
 extern "C" difa_status_t difa_plan_destroy(difa_plan_t* p) {
@@ -302,6 +332,23 @@ extern "C" difa_status_t difa_plan_destroy(difa_plan_t* p) {
     return DIFA_OK;
 }
 
+extern "C" difa_status_t difa_device_info(int32_t device, int32_t* compute_units, int32_t* clock_khz,
+                                          int32_t* memory_clock_khz, int32_t* l2_bytes, char* arch, int32_t arch_len) {
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) != hipSuccess || device < 0 || device >= n_dev) return DIFA_ERR_INVALID_ARG;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) != hipSuccess) return DIFA_ERR_HIP;
+    if (compute_units) *compute_units = prop.multiProcessorCount;
+    if (clock_khz) *clock_khz = prop.clockRate;
+    if (memory_clock_khz) *memory_clock_khz = prop.memoryClockRate;
+    if (l2_bytes) *l2_bytes = prop.l2CacheSize;
+    if (arch && arch_len > 0) {
+        strncpy(arch, prop.gcnArchName, (size_t)arch_len - 1);
+        arch[arch_len - 1] = 0;
+    }
+    return DIFA_OK;
+}
+
 extern "C" difa_status_t difa_plan_timing_enable(difa_plan_t* p, int32_t enable) {
     if (!p) return DIFA_ERR_INVALID_ARG;
     p->timing = enable != 0;
@@ -310,6 +357,7 @@ extern "C" difa_status_t difa_plan_timing_enable(difa_plan_t* p, int32_t enable)
 
 extern "C" difa_status_t difa_plan_timing_read(difa_plan_t* p, double* attn_ms, double* copy_ms,
                                                int64_t* launches, int32_t reset) {
+    return guarded(p, [&]() -> difa_status_t {
     if (!p) return DIFA_ERR_INVALID_ARG;
     DeviceGuard guard;
     hipError_t e = guard.enter(p->desc.device);
@@ -320,9 +368,11 @@ extern "C" difa_status_t difa_plan_timing_read(difa_plan_t* p, double* attn_ms, 
     if (launches) *launches = p->launches;
     if (reset) { p->attn_ms = 0; p->copy_ms = 0; p->launches = 0; }
     return DIFA_OK;
+    });
 }
 
 extern "C" difa_status_t difa_plan_timing_read_head_rse(difa_plan_t* p, double* rse_ms, int64_t* launches, int32_t reset) {
+    return guarded(p, [&]() -> difa_status_t {
     if (!p) return DIFA_ERR_INVALID_ARG;
     DeviceGuard guard;
     hipError_t e = guard.enter(p->desc.device);
@@ -332,6 +382,7 @@ extern "C" difa_status_t difa_plan_timing_read_head_rse(difa_plan_t* p, double* 
     if (launches) *launches = p->rse_launches;
     if (reset) { p->rse_ms = 0; p->rse_launches = 0; }
     return DIFA_OK;
+    });
 }
 
 namespace {
@@ -546,27 +597,20 @@ extern "C" difa_status_t difa_joint_attention(difa_plan_t* p, const void* q, con
                                               void* out, const void* cache, const int32_t* head_plan,
                                               int32_t n_text, int32_t n_img, const int32_t* window,
                                               void* stream) {
-    try {
-        return joint_attention_impl(p, q, k, v, out, cache, head_plan, n_text, n_img, window, stream, false);
-    } catch (const std::bad_alloc&) {
-        return fail(p, DIFA_ERR_ALLOC, "out of host memory");
-    }
+    return guarded(p, [&]() { return joint_attention_impl(p, q, k, v, out, cache, head_plan, n_text, n_img, window, stream, false); });
 }
 
 extern "C" difa_status_t difa_joint_attention_static(difa_plan_t* p, const void* q, const void* k, const void* v,
                                                      void* out, const void* cache, const int32_t* head_plan,
                                                      int32_t n_text, int32_t n_img, const int32_t* window,
                                                      void* stream) {
-    try {
-        return joint_attention_impl(p, q, k, v, out, cache, head_plan, n_text, n_img, window, stream, true);
-    } catch (const std::bad_alloc&) {
-        return fail(p, DIFA_ERR_ALLOC, "out of host memory");
-    }
+    return guarded(p, [&]() { return joint_attention_impl(p, q, k, v, out, cache, head_plan, n_text, n_img, window, stream, true); });
 }
 
 // Influence[h] = RSE(O[h], O'[h]) of Alg. 1 (Sec. 3.4.1, Eq. 1): one streaming pass over both tensors.
 extern "C" difa_status_t difa_head_rse(difa_plan_t* p, const void* y_m, const void* y_o, int32_t n_tokens,
                                        float* rse_out, void* stream_v) {
+    return guarded(p, [&]() -> difa_status_t {
     if (!p) return DIFA_ERR_INVALID_ARG;
     if (!y_m || !y_o || !rse_out) return fail(p, DIFA_ERR_INVALID_ARG, "y_m, y_o and rse_out must not be NULL");
     if (n_tokens < 1 || n_tokens > p->desc.max_tokens)
@@ -593,4 +637,5 @@ extern "C" difa_status_t difa_head_rse(difa_plan_t* p, const void* y_m, const vo
     if (p->timing) { (void)hipEventRecord(tp.stop, stream); p->pending.push_back(tp); }
     if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("influence-metric launch", e));
     return DIFA_OK;
+    });
 }

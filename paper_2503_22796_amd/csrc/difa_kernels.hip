@@ -201,10 +201,10 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
     auto dma_part = [&](int tensor, int u, unsigned tb, unsigned dst) __attribute__((always_inline)) {
         if (tensor == 0)
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                         :: "s"(dst + (unsigned)(u * RPI * D * 2)), "v"(gk[u] + tb), "s"(krsrc));
+                         :: "s"(dst + (unsigned)(u * RPI * D * 2)), "v"(gk[u] + tb), "s"(krsrc) : "m0");
         else
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                         :: "s"(dst + (unsigned)(u * RPI * D * 2)), "v"(gv[u] + tb), "s"(vrsrc));
+                         :: "s"(dst + (unsigned)(u * RPI * D * 2)), "v"(gv[u] + tb), "s"(vrsrc) : "m0");
     };
     const unsigned wave_lds = wave_u * (unsigned)(NDMA * RPI * D * 2);     // this wavefront's rows inside a stage
     // all loads done / all but the 2*NDMA youngest (= the tiles issued during the current iteration) done

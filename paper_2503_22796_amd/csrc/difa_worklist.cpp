@@ -9,6 +9,7 @@
 #include <stdint.h>
 
 #include <algorithm>
+#include <new>
 #include <vector>
 
 #include "difa.h"
@@ -72,12 +73,13 @@ extern "C" int32_t difa_tile_shape(int32_t head_dim, int32_t dtype, int32_t* bm,
     return 0;
 }
 
-extern "C" difa_status_t difa_worklist_build(int32_t batch, int32_t heads, const int32_t* head_plan,
-                                             const int32_t* window, int32_t n_text, int32_t n_img,
-                                             int32_t bm, int32_t bn, int32_t n_xcd, uint32_t flags,
-                                             difa_work_item_t* items,
-                                             int32_t capacity, int32_t* n_items_out,
-                                             int32_t* copy_heads, int32_t* n_copy_out) {
+namespace {
+difa_status_t worklist_build(int32_t batch, int32_t heads, const int32_t* head_plan,
+                             const int32_t* window, int32_t n_text, int32_t n_img,
+                             int32_t bm, int32_t bn, int32_t n_xcd, uint32_t flags,
+                             difa_work_item_t* items,
+                             int32_t capacity, int32_t* n_items_out,
+                             int32_t* copy_heads, int32_t* n_copy_out) {
     if (!head_plan || !n_items_out || batch < 1 || heads < 1 || n_text < 0 || n_img < 0 ||
         bm < 1 || bn < 1 || n_xcd < 1 || n_xcd > 64 || capacity < 0 || (capacity > 0 && !items) ||
         (flags & ~(uint32_t)(DIFA_FLAG_BLOCK_BAND | DIFA_FLAG_IMAGE_FIRST)) != 0)
@@ -216,6 +218,21 @@ extern "C" difa_status_t difa_worklist_build(int32_t batch, int32_t heads, const
     if ((int64_t)recs.size() > capacity) return capacity == 0 && !items ? DIFA_OK : DIFA_ERR_ALLOC;
     std::copy(recs.begin(), recs.end(), items);
     return DIFA_OK;
+}
+}  // namespace
+
+extern "C" difa_status_t difa_worklist_build(int32_t batch, int32_t heads, const int32_t* head_plan,
+                                             const int32_t* window, int32_t n_text, int32_t n_img,
+                                             int32_t bm, int32_t bn, int32_t n_xcd, uint32_t flags,
+                                             difa_work_item_t* items,
+                                             int32_t capacity, int32_t* n_items_out,
+                                             int32_t* copy_heads, int32_t* n_copy_out) {
+    try {
+        return worklist_build(batch, heads, head_plan, window, n_text, n_img, bm, bn, n_xcd, flags, items, capacity,
+                              n_items_out, copy_heads, n_copy_out);
+    } catch (const std::bad_alloc&) {
+        return DIFA_ERR_ALLOC;
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -387,10 +404,11 @@ DiePlan fill_in_order(const std::vector<difa_work_item_t>& q, int per_die, int64
 
 }  // namespace
 
-extern "C" difa_status_t difa_schedule_build(const difa_work_item_t* items, int32_t n_items, int32_t n_wg,
-                                             int32_t n_xcd, difa_segment_t* segs, int32_t seg_capacity,
-                                             int32_t* wg_begin, int32_t* n_segs_out, difa_merge_item_t* merges,
-                                             int32_t merge_capacity, int32_t* n_merges_out, int32_t* n_slots_out) {
+namespace {
+difa_status_t schedule_build(const difa_work_item_t* items, int32_t n_items, int32_t n_wg,
+                             int32_t n_xcd, difa_segment_t* segs, int32_t seg_capacity,
+                             int32_t* wg_begin, int32_t* n_segs_out, difa_merge_item_t* merges,
+                             int32_t merge_capacity, int32_t* n_merges_out, int32_t* n_slots_out) {
     if (n_items < 0 || (n_items > 0 && !items) || n_wg < 1 || n_xcd < 1 || n_wg % n_xcd != 0 || !wg_begin ||
         !n_segs_out || !n_merges_out || !n_slots_out || seg_capacity < 0 || merge_capacity < 0 ||
         (seg_capacity > 0 && !segs) || (merge_capacity > 0 && !merges))
@@ -489,4 +507,17 @@ extern "C" difa_status_t difa_schedule_build(const difa_work_item_t* items, int3
     wg_begin[n_wg] = at;
     std::copy(merge_list.begin(), merge_list.end(), merges);
     return DIFA_OK;
+}
+}  // namespace
+
+extern "C" difa_status_t difa_schedule_build(const difa_work_item_t* items, int32_t n_items, int32_t n_wg,
+                                             int32_t n_xcd, difa_segment_t* segs, int32_t seg_capacity,
+                                             int32_t* wg_begin, int32_t* n_segs_out, difa_merge_item_t* merges,
+                                             int32_t merge_capacity, int32_t* n_merges_out, int32_t* n_slots_out) {
+    try {
+        return schedule_build(items, n_items, n_wg, n_xcd, segs, seg_capacity, wg_begin, n_segs_out, merges,
+                              merge_capacity, n_merges_out, n_slots_out);
+    } catch (const std::bad_alloc&) {
+        return DIFA_ERR_ALLOC;
+    }
 }

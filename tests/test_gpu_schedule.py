@@ -65,6 +65,92 @@ def test_flux_2k_schedule_three_steps_two_layers():
     print(f"flux_2k schedule ({len(layers)} layers x {steps} steps): max_abs_err={worst:.3e}", flush=True)
 
 
+def test_flux_2k_schedule_all_28_steps_of_four_layers():
+    """The 57-layer x 28-step schedule on four of its layers, every step: each layer's plan object sees 28
+    distinct plans (more than it keeps resident, so work lists are evicted and recompiled at the 2K size).
+    Every call: each cached head bit-identical to the layer's previous output.  Twelve sampled (layer, step)
+    pairs, the last step among them: computed heads against the oracle on sampled rows.  A head that stays
+    cached for three steps or more in a row still carries, bit for bit, the output of the step that last
+    computed it, and that output agrees with the oracle's value for that earlier step."""
+    from oracle import difa_oracle as O
+    from paper_2503_22796_amd import binding as B
+    base = W.flux_2k_mixed()
+    L, T = 57, 28
+    hp, win = W.schedule_plans(L, T, base.H, seed=5)
+    layers = [0, 19, 33, 56]
+    dev = torch.device("cuda:0")
+    shape = (base.B, base.H, base.N, base.D)
+    rows = boundary_rows(base.n_text, base.n_img, [512, 1024, 2048], extra=230, seed=11)
+    assert len(rows) >= 256
+    # a run of at least three cached steps of one head in one of the layers, the longest there is
+    run = None
+    for l in layers:
+        for h in range(base.H):
+            t = 1
+            while t < T:
+                if hp[l, t, h] != CACHE:
+                    t += 1
+                    continue
+                t0 = t
+                while t < T and hp[l, t, h] == CACHE:
+                    t += 1
+                if t - t0 >= 3 and (run is None or t - t0 > run[3] - run[2]):
+                    run = (l, h, t0, t)            # cached on steps t0 .. t-1, last computed at step t0 - 1
+    assert run is not None, "the seeded schedule has no head cached three steps in a row in these layers"
+    checked = {(0, 0), (0, 1), (19, 2), (33, 5), (56, 9), (0, 13), (19, 17), (33, 21), (56, 24), (0, 27), (33, 27),
+               (run[0], run[2] - 1)}
+    assert len(checked) == 12
+    gen = torch.Generator(device=dev)
+    pos = torch.from_numpy(W.positional_term(base.n_img, base.D)).to(dev)
+    plans = {l: B.difa_plan_create(base.B, base.H, base.D, max_tokens=base.N) for l in layers}
+    bufs = {l: [torch.full(shape, float("nan"), dtype=torch.bfloat16, device=dev) for _ in range(2)] for l in layers}
+    kept, worst = None, 0.0
+    try:
+        for t in range(T):
+            gen.manual_seed(1000 + t)              # the step's Q, K, V: seeded draws made on the device
+            trio = []
+            for _ in range(3):
+                x = torch.randn(shape, device=dev, dtype=torch.float32, generator=gen)
+                x[:, :, base.n_text:, :] += pos
+                trio.append(x.to(torch.bfloat16))
+            qd, kd, vd = trio
+            host = None
+            for l in layers:
+                out, cache = bufs[l][(t + 1) % 2], bufs[l][t % 2]
+                out.fill_(float("nan"))
+                B.difa_joint_attention(plans[l], qd, kd, vd, out, cache if t > 0 else None, hp[l, t],
+                                       base.n_text, base.n_img, win[l, t])
+                torch.cuda.synchronize()
+                for h in range(base.H):
+                    if hp[l, t, h] == CACHE:
+                        assert torch.equal(out[:, h].view(torch.int16), cache[:, h].view(torch.int16)), \
+                            f"layer {l} step {t} head {h}: cached head differs from the previous step"
+                if (l, t) in checked:
+                    if host is None:
+                        host = tuple(x.cpu() for x in trio)
+                    got = out[:, :, rows].cpu()
+                    ref, _, _ = O.joint_attention(*host, torch.zeros(shape, dtype=torch.bfloat16), hp[l, t], win[l, t],
+                                                  base.n_text, base.n_img, rows=rows)
+                    for h in range(base.H):
+                        if hp[l, t, h] == CACHE:
+                            continue
+                        assert torch.isfinite(got[:, h].float()).all(), f"layer {l} step {t} head {h}: unwritten rows"
+                        err = float((got[:, h].double() - ref[:, h]).abs().max())
+                        assert err <= TOL_BF16, f"layer {l} step {t} head {h}: max abs err {err:.3e}"
+                        worst = max(worst, err)
+                    if (l, t) == (run[0], run[2] - 1):
+                        kept = out[:, run[1]].clone()          # the head's last computed output, checked just above
+                if l == run[0] and run[2] <= t < run[3]:
+                    assert torch.equal(out[:, run[1]].view(torch.int16), kept.view(torch.int16)), \
+                        f"layer {l} head {run[1]}: cached since step {run[2]}, differs at step {t} from step {run[2] - 1}"
+    finally:
+        for p in plans.values():
+            B.difa_plan_destroy(p)
+    print(f"flux_2k schedule, layers {layers} x {T} steps: {len(checked)} (layer, step) pairs against the oracle on "
+          f"{len(rows)} rows/head, max_abs_err={worst:.3e}; head {run[1]} of layer {run[0]} cached on steps "
+          f"{run[2]}..{run[3] - 1}", flush=True)
+
+
 def test_small_schedule_many_plans_per_layer():
     # more distinct plans per layer than the plan object memoises, an odd token count, head_dim 64
     H, layers, steps = 6, 3, 11

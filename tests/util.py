@@ -5,7 +5,18 @@ import torch
 FULL, ARROW, CACHE = 0, 1, 2
 TOL_BF16 = 2e-2   # max-abs bar for bf16 inputs, fp32 accumulation
 TOL_F32 = 1e-5    # max-abs bar for the fp32 debug path
-
+# Second, magnitude-aware bars of the bf16 path, per head:
+#   every element:  |err| <= REL_BF16 * |ref| + ABS_BF16
+#   on average:     rms(err) <= RMS_REL_BF16 * rms(ref) + RMS_ABS_BF16
+# The output is rounded to bf16: an error of up to half a step, 2^-9 of the value's power of two, i.e. at most
+# 2^-8 |ref| and 2^-8 / sqrt(3) |ref| = 0.0023 |ref| in the root mean square.  The weights are rounded to bf16
+# before they meet V (2^-9 relative each, independent): sum_j p_j d_j (v_j - out) / l, which for a row carried
+# by two keys whose values differ by up to 6 reaches 2^-9 * 6 = 1.2e-2 and does not shrink with the result;
+# the worst seen against the fp64 oracle over the named configurations (2K layers on all rows) is 6.8e-3.
+REL_BF16 = 2.0 ** -7
+ABS_BF16 = 1e-2
+RMS_REL_BF16 = 2.0 ** -8
+RMS_ABS_BF16 = 1e-3
 
 def gpu_joint_attention(q, k, v, cache, head_plan, window, n_text, n_img, scale=0.0, layout="bhnd",
                         poison=True, stream=None, plan=None, alias_out_to_cache=False, flags=0):
@@ -59,10 +70,29 @@ def check_against_oracle(out, q, k, v, cache, head_plan, window, n_text, n_img, 
         else:
             g = got[:, h].double()
             assert torch.isfinite(g).all(), f"head {h}: non-finite output (unwritten or NaN rows)"
-            err = float((g - ref[:, h]).abs().max())
+            diff = (g - ref[:, h]).abs()
+            err = float(diff.max())
             assert err <= tol, f"head {h} (mode {hp[h]}, w {window[h]}): max abs err {err:.3e} > {tol}"
+            if got.dtype == torch.bfloat16 and tol == TOL_BF16:
+                excess = float((diff - REL_BF16 * ref[:, h].abs()).max())
+                assert excess <= ABS_BF16, \
+                    f"head {h} (mode {hp[h]}, w {window[h]}): error exceeds {REL_BF16:.4f}*|ref| by {excess:.3e} > {ABS_BF16}"
+                check_against_oracle.worst_excess = max(getattr(check_against_oracle, "worst_excess", -1.0), excess)
+                rms_err, rms_ref = float(diff.pow(2).mean().sqrt()), float(ref[:, h].pow(2).mean().sqrt())
+                ratio = rms_err / (RMS_REL_BF16 * rms_ref + RMS_ABS_BF16)
+                check_against_oracle.worst_rms = max(getattr(check_against_oracle, "worst_rms", 0.0), ratio)
+                assert ratio <= 1.0, \
+                    f"head {h} (mode {hp[h]}, w {window[h]}): rms error {rms_err:.3e} against rms(ref) {rms_ref:.3e}"
             worst = max(worst, err)
     return worst
+
+
+def same_result_bf16(a, b):
+    """Two bf16 results of the same computation obtained along different routes (another schedule, another
+    token order).  Their reference rows differ, so their weights are rounded independently: each is within the
+    element bar of the exact result, and the two are within twice that of each other."""
+    a, b = a.double(), b.double()
+    return bool(((a - b).abs() <= 2 * (REL_BF16 * torch.maximum(a.abs(), b.abs()) + ABS_BF16)).all())
 
 
 def boundary_rows(n_text, n_img, windows, bm=128, extra=64, seed=0):
