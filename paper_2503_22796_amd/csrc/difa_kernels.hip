@@ -660,19 +660,49 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
     // V tile idx+2 and, before the next barrier, waits for the loads issued one iteration earlier
     // (K tile idx+2, V tile idx+1).  K tile p is last read in the first half of iteration p, V tile p in
     // the first half of iteration p+1, so both rings are four stages deep.
-    for (int idx = 1; idx < n_iter; ++idx) {
-        v_prv = v_cur;
-        bump(k_cur); bump(k_nxt); bump(k_ld); bump(v_cur); bump(v_ld);
+    // The loop body exists four times, once per ring stage the current tile can sit in: with the stage a
+    // compile-time constant the ring offsets become immediate operands of the LDS reads, which saves the
+    // two dozen address additions a tile costs when the stage is a run-time value, and the stage
+    // bookkeeping itself.  The loop is entered at the copy the segment's second tile needs.
+    auto iteration = [&](auto stage_c, int idx) __attribute__((always_inline)) {
+        constexpr int P = decltype(stage_c)::value;         // ring stage of tile idx
+        constexpr int KC = P * TILE, KN = ((P + 1) & 3) * TILE, KL = ((P + 3) & 3) * TILE;
+        constexpr int VP = ((P + 3) & 3) * TILE, VC = P * TILE, VL = ((P + 2) & 3) * TILE;
         msk_cur = msk_nxt;
         msk_nxt = pos_masked(idx + 1);
         tb_v = tb_k;
         tb_k = tile_offset(idx + 3);
         __syncthreads();    // the tiles waited for last are in LDS for everyone; the stages loaded next are no longer read
-        half_step(s0, s1, pb, pa, kptr(k_cur, 1), kptr(k_nxt, 0), vptr(v_prv, 1), vptr(v_cur, 0), true,
-                  msk_cur, 2 * idx + 1, 0, tb_k, k_lds + (unsigned)(k_ld * 2) + wave_lds);
-        half_step(s1, s0, pa, pb, kptr(k_nxt, 0), kptr(k_nxt, 1), vptr(v_cur, 0), vptr(v_cur, 1), true,
-                  msk_nxt, 2 * idx + 2, 1, tb_v, v_lds + (unsigned)(v_ld * 2) + wave_lds);
+        half_step(s0, s1, pb, pa, kptr(KC, 1), kptr(KN, 0), vptr(VP, 1), vptr(VC, 0), true,
+                  msk_cur, 2 * idx + 1, 0, tb_k, k_lds + (unsigned)(KL * 2) + wave_lds);
+        half_step(s1, s0, pa, pb, kptr(KN, 0), kptr(KN, 1), vptr(VC, 0), vptr(VC, 1), true,
+                  msk_nxt, 2 * idx + 2, 1, tb_v, v_lds + (unsigned)(VL * 2) + wave_lds);
         dma_wait_older();
+    };
+    {
+        int idx = 1;
+        int phase = (sbase + 1) & 3;
+        while (idx < n_iter) {
+            switch (phase) {
+                case 0:
+                    iteration(std::integral_constant<int, 0>(), idx);
+                    if (++idx >= n_iter) break;
+                    [[fallthrough]];
+                case 1:
+                    iteration(std::integral_constant<int, 1>(), idx);
+                    if (++idx >= n_iter) break;
+                    [[fallthrough]];
+                case 2:
+                    iteration(std::integral_constant<int, 2>(), idx);
+                    if (++idx >= n_iter) break;
+                    [[fallthrough]];
+                default:
+                    iteration(std::integral_constant<int, 3>(), idx);
+                    ++idx;
+            }
+            phase = 0;
+        }
+        v_cur = ((sbase + n_iter - 1) & 3) * TILE;          // stage of the last tile, for its second block's P V
     }
     // The key loop is over: the K stages and all V stages but the last tile's are free.  Loads past the
     // segment's end may still be depositing zeros, and other wavefronts may still be reading: wait for
