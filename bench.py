@@ -375,6 +375,18 @@ def main():
         out["plan_scaling"] = {"t_mixed_over_t_full": wall_ms / full["ms_per_step"],
                                "kernel_t_mixed_over_t_full": attn_avg / full["avg_kernel_ms"],
                                "flop_mixed_over_flop_full": fl["computed"] / fl_full["computed"]}
+        # The same all-full layer on all-zero operands: identical instruction stream, identical clock count,
+        # but the matrix cores switch next to nothing, so the chip holds its clock.  The ratio of the two times
+        # is what the power limit costs on realistic operand data.
+        zq = torch.zeros_like(qd)
+        zero, _ = side_run("flux_2k_full", zq, zq, zq, cd, side_steps, 5)
+        out["power_limit_probe"] = {
+            "workload": "flux_2k_full", "ms_per_step_workload_data": full["ms_per_step"],
+            "ms_per_step_zero_operands": zero["ms_per_step"],
+            "time_ratio_zero_over_data": zero["ms_per_step"] / full["ms_per_step"],
+            "frac_of_bf16_peak_zero_operands": zero["frac_of_bf16_peak_kernel"],
+            "what": "same kernel, same launch, Q = K = V = 0: the time the schedule takes when the clock is not lowered"}
+        del zq
         out["all_cached"], _ = side_run("flux_2k_cache", qd, kd, vd, cd, side_steps, 5)
         out["arrow_w128"], _ = side_run("flux_2k_arrow_w128", qd, kd, vd, cd, side_steps, 5)
 
