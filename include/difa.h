@@ -37,7 +37,8 @@ typedef enum {
     DIFA_ERR_HIP = 4          /* a HIP runtime call failed; text in difa_last_error()     */
 } difa_status_t;
 
-enum { DIFA_HEAD_FULL = 0, DIFA_HEAD_ARROW = 1, DIFA_HEAD_CACHE = 2 };
+enum { DIFA_HEAD_FULL = 0, DIFA_HEAD_ARROW = 1, DIFA_HEAD_CACHE = 2,
+       DIFA_HEAD_ARROW_RESIDUAL = 3 /* only with difa_joint_attention_residual, see there */ };
 enum { DIFA_DTYPE_BF16 = 0, DIFA_DTYPE_F32 = 1 }; /* F32 = slow all-fp32 debug path */
 enum { DIFA_LAYOUT_BHND = 0, DIFA_LAYOUT_BNHD = 1 };
 /* Plan flags.  DIFA_FLAG_BLOCK_BAND selects the block-granular band of the paper's own kernel
@@ -128,6 +129,35 @@ difa_status_t difa_joint_attention_static(difa_plan_t* plan, const void* q, cons
                                           int32_t n_text, int32_t n_img, const int32_t* window,
                                           void* stream);
 
+/*
+ * Arrow attention with residual sharing, the optional method the paper keeps from its predecessor (Sec. 2.4;
+ * evaluated in Sec. 4.6.1 and Table 4; the technique itself is defined in the predecessor's paper, so the
+ * reading is this library's): at a refresh step a head runs full attention and arrow attention and keeps the
+ * difference of the two outputs,
+ *     r = O_full - O_arrow                  (difa_residual_store; rounded once, to the element type);
+ * at the following steps it runs arrow attention only and adds the kept difference before the result is
+ * rounded,
+ *     O = ArrowAttention(Q, K, V; w) + r    (a head in mode DIFA_HEAD_ARROW_RESIDUAL).
+ *
+ * difa_joint_attention_residual is difa_joint_attention with one more tensor:
+ *   residual   DEVICE, shape/layout/dtype of `out`, read-only, read only for DIFA_HEAD_ARROW_RESIDUAL heads
+ *              (their window comes from `window` as for ARROW heads).  May be NULL iff no head has that mode.
+ *              Must not alias `out`.
+ * Everything else -- arguments, asynchrony, errors -- as difa_joint_attention, which itself rejects the
+ * mode with INVALID_ARG.
+ *
+ * difa_residual_store writes residual[e] = o_full[e] - o_arrow[e] for every element of the plan's tensor
+ * shape with n_tokens tokens (all heads; a caller that shares the residual of some heads only ignores the
+ * rest).  The three tensors are DEVICE, 16-byte aligned, of the plan's dtype; `residual` may alias neither
+ * input.  Asynchronous on `stream`.  Returns DIFA_OK, INVALID_ARG or HIP.
+ */
+difa_status_t difa_joint_attention_residual(difa_plan_t* plan, const void* q, const void* k, const void* v,
+                                            void* out, const void* cache, const void* residual,
+                                            const int32_t* head_plan, int32_t n_text, int32_t n_img,
+                                            const int32_t* window, void* stream);
+difa_status_t difa_residual_store(difa_plan_t* plan, const void* o_full, const void* o_arrow, void* residual,
+                                  int32_t n_tokens, void* stream);
+
 /* Release the object and its buffers (waits for the device to finish work that uses them).
  * NULL is a no-op that returns DIFA_OK.  (This call and the two below manage the object and report
  * errors; they correspond to no passage of the paper.) */
@@ -164,7 +194,9 @@ typedef struct {
     int32_t nm1_end;
     int32_t window;    /* half-width for an ARROW head, -1 for a FULL head                */
     int32_t n_tiles;   /* number of key tiles visited (the record's cost)                 */
+    int32_t flags;     /* DIFA_ITEM_ADD_RESIDUAL: the head's kept difference is added     */
 } difa_work_item_t;
+enum { DIFA_ITEM_ADD_RESIDUAL = 1 };
 
 /* Tile shape (query rows bm, keys bn) the kernels use for a head_dim/dtype; 0 on success. */
 int32_t difa_tile_shape(int32_t head_dim, int32_t dtype, int32_t* bm, int32_t* bn);
@@ -209,7 +241,7 @@ typedef struct {
     int32_t n_parts;             /* number of pieces the record was cut into (1 for a whole record)    */
     int32_t first_slot;          /* scratch slot of the record's first piece (its pieces use consecutive
                                     slots), -1 for a whole record                                      */
-    int32_t reserved;            /* 0; the record is 64 bytes                                          */
+    int32_t flags;               /* DIFA_ITEM_* bits of the record; the record is 64 bytes              */
 } difa_segment_t;
 
 typedef struct {

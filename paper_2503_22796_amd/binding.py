@@ -12,7 +12,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("DIFA_LIBRARY", os.path.join(HERE, "libdifa.so"))   # override: another build of the same ABI
 
 DIFA_OK, DIFA_ERR_INVALID_ARG, DIFA_ERR_UNSUPPORTED, DIFA_ERR_ALLOC, DIFA_ERR_HIP = range(5)
-DIFA_HEAD_FULL, DIFA_HEAD_ARROW, DIFA_HEAD_CACHE = 0, 1, 2
+DIFA_HEAD_FULL, DIFA_HEAD_ARROW, DIFA_HEAD_CACHE, DIFA_HEAD_ARROW_RESIDUAL = 0, 1, 2, 3
+DIFA_ITEM_ADD_RESIDUAL = 1
 DIFA_DTYPE_BF16, DIFA_DTYPE_F32 = 0, 1
 DIFA_LAYOUT_BHND, DIFA_LAYOUT_BNHD = 0, 1
 DIFA_FLAG_BLOCK_BAND = 1
@@ -28,13 +29,13 @@ class difa_plan_desc_t(ctypes.Structure):
 class difa_work_item_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("bh", "q_tile", "kv0_end", "nm0_end", "kv1_begin", "kv1_end", "nm1_begin", "nm1_end",
-                 "window", "n_tiles")]
+                 "window", "n_tiles", "flags")]
 
 
 class difa_segment_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("bh", "q_tile", "kv0_end", "nm0_end", "kv1_begin", "kv1_end", "nm1_begin", "nm1_end",
-                 "window", "pos_begin", "pos_end", "part_slot", "merge_idx", "n_parts", "first_slot", "reserved")]
+                 "window", "pos_begin", "pos_end", "part_slot", "merge_idx", "n_parts", "first_slot", "flags")]
 
 
 class difa_merge_item_t(ctypes.Structure):
@@ -53,6 +54,10 @@ def _load():
     L.difa_joint_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp]
     L.difa_joint_attention_static.restype = ctypes.c_int
     L.difa_joint_attention_static.argtypes = L.difa_joint_attention.argtypes
+    L.difa_joint_attention_residual.restype = ctypes.c_int
+    L.difa_joint_attention_residual.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp]
+    L.difa_residual_store.restype = ctypes.c_int
+    L.difa_residual_store.argtypes = [vp, vp, vp, vp, i32, vp]
     L.difa_plan_destroy.restype = ctypes.c_int
     L.difa_plan_destroy.argtypes = [vp]
     L.difa_status_string.restype = ctypes.c_char_p
@@ -195,6 +200,30 @@ def difa_joint_attention(plan, q, k, v, out, cache, head_plan, n_text, n_img, wi
     st = (_entry or lib.difa_joint_attention)(plan, _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(cache),
                                   hp.ctypes.data if hp is not None else None, int(n_text), int(n_img),
                                   win.ctypes.data if win is not None else None, ctypes.c_void_p(stream))
+    if st != DIFA_OK:
+        raise DifaError(st, difa_last_error(plan))
+
+
+def difa_joint_attention_residual(plan, q, k, v, out, cache, residual, head_plan, n_text, n_img, window, stream=None):
+    """difa_joint_attention with the kept differences of the DIFA_HEAD_ARROW_RESIDUAL heads (`residual`, may be None)."""
+    import torch
+    hp, win = _i32(head_plan), _i32(window)
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device).cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    st = lib.difa_joint_attention_residual(plan, _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(cache), _ptr(residual),
+                                           hp.ctypes.data if hp is not None else None, int(n_text), int(n_img),
+                                           win.ctypes.data if win is not None else None, ctypes.c_void_p(stream))
+    if st != DIFA_OK:
+        raise DifaError(st, difa_last_error(plan))
+
+
+def difa_residual_store(plan, o_full, o_arrow, residual, n_tokens, stream=None):
+    """residual = o_full - o_arrow, element by element (device tensors of the plan's shape and dtype), asynchronous."""
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream(o_full.device).cuda_stream
+    st = lib.difa_residual_store(plan, _ptr(o_full), _ptr(o_arrow), _ptr(residual), int(n_tokens), ctypes.c_void_p(s))
     if st != DIFA_OK:
         raise DifaError(st, difa_last_error(plan))
 

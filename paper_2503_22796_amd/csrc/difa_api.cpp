@@ -392,7 +392,8 @@ namespace {
 difa_status_t joint_attention_impl(difa_plan_t* p, const void* q, const void* k, const void* v,
                                    void* out, const void* cache, const int32_t* head_plan,
                                    int32_t n_text, int32_t n_img, const int32_t* window,
-                                   void* stream_v, bool static_scratch) {
+                                   void* stream_v, bool static_scratch, const void* residual = nullptr,
+                                   bool residual_entry = false) {
     if (!p) return DIFA_ERR_INVALID_ARG;
     if (!q || !k || !v || !out || !head_plan)
         return fail(p, DIFA_ERR_INVALID_ARG, "q, k, v, out and head_plan must not be NULL");
@@ -402,18 +403,25 @@ difa_status_t joint_attention_impl(difa_plan_t* p, const void* q, const void* k,
         return fail(p, DIFA_ERR_INVALID_ARG, "n_text + n_img must be in [1, max_tokens]");
     if (out == q || out == k || out == v) return fail(p, DIFA_ERR_INVALID_ARG, "out must not alias q, k or v");
     const int H = p->desc.heads, B = p->desc.batch, D = p->desc.head_dim, N = (int)n64;
-    bool any_cache = false;
+    bool any_cache = false, any_residual = false;
     for (int h = 0; h < H; ++h) {
         const int mode = head_plan[h];
-        if (mode != DIFA_HEAD_FULL && mode != DIFA_HEAD_ARROW && mode != DIFA_HEAD_CACHE)
-            return fail(p, DIFA_ERR_INVALID_ARG, "head_plan entries must be DIFA_HEAD_FULL, _ARROW or _CACHE");
-        if (mode == DIFA_HEAD_ARROW && !window)
+        const bool banded = mode == DIFA_HEAD_ARROW || mode == DIFA_HEAD_ARROW_RESIDUAL;
+        if (mode == DIFA_HEAD_ARROW_RESIDUAL && !residual_entry)
+            return fail(p, DIFA_ERR_INVALID_ARG, "DIFA_HEAD_ARROW_RESIDUAL needs difa_joint_attention_residual");
+        if (mode != DIFA_HEAD_FULL && !banded && mode != DIFA_HEAD_CACHE)
+            return fail(p, DIFA_ERR_INVALID_ARG, "head_plan entries must be DIFA_HEAD_FULL, _ARROW, _CACHE or _ARROW_RESIDUAL");
+        if (banded && !window)
             return fail(p, DIFA_ERR_INVALID_ARG, "window must not be NULL when a head is ARROW");
-        if (mode == DIFA_HEAD_ARROW && window[h] < 0)
+        if (banded && window[h] < 0)
             return fail(p, DIFA_ERR_INVALID_ARG, "window of an ARROW head must be >= 0");
         any_cache |= (mode == DIFA_HEAD_CACHE);
+        any_residual |= (mode == DIFA_HEAD_ARROW_RESIDUAL);
     }
     if (any_cache && !cache) return fail(p, DIFA_ERR_INVALID_ARG, "cache must not be NULL when a head is CACHE");
+    if (any_residual && !residual)
+        return fail(p, DIFA_ERR_INVALID_ARG, "residual must not be NULL when a head is ARROW_RESIDUAL");
+    if (any_residual && residual == out) return fail(p, DIFA_ERR_INVALID_ARG, "residual must not alias out");
     if (p->desc.dtype == DIFA_DTYPE_BF16) {
         // the bf16 kernel addresses a head's K and V through 32-bit byte offsets (and uses offset 2^31 to
         // mean "no tile"): the distance from a head's first to its last element must stay below 2 GiB
@@ -435,7 +443,7 @@ difa_status_t joint_attention_impl(difa_plan_t* p, const void* q, const void* k,
     int32_t* key = p->keys.data() + (size_t)kSlots * key_len;
     for (int h = 0; h < H; ++h) {
         key[2 * h] = head_plan[h];
-        key[2 * h + 1] = head_plan[h] == DIFA_HEAD_ARROW ? window[h] : 0;
+        key[2 * h + 1] = head_plan[h] == DIFA_HEAD_ARROW || head_plan[h] == DIFA_HEAD_ARROW_RESIDUAL ? window[h] : 0;
     }
     key[2 * H] = n_text;
     key[2 * H + 1] = n_img;
@@ -532,6 +540,7 @@ difa_status_t joint_attention_impl(difa_plan_t* p, const void* q, const void* k,
         const char* db = (const char*)slot->d_buf;
         difa::AttnArgs a{};
         a.q = q; a.k = k; a.v = v; a.out = out;
+        a.residual = residual;
         a.items = (const difa_work_item_t*)(db + slot->items_off);
         a.segs = (const difa_segment_t*)(db + slot->segs_off);
         a.wg_begin = (const int32_t*)(db + slot->wg_off);
@@ -605,6 +614,35 @@ extern "C" difa_status_t difa_joint_attention_static(difa_plan_t* p, const void*
                                                      int32_t n_text, int32_t n_img, const int32_t* window,
                                                      void* stream) {
     return guarded(p, [&]() { return joint_attention_impl(p, q, k, v, out, cache, head_plan, n_text, n_img, window, stream, true); });
+}
+
+extern "C" difa_status_t difa_joint_attention_residual(difa_plan_t* p, const void* q, const void* k, const void* v,
+                                                       void* out, const void* cache, const void* residual,
+                                                       const int32_t* head_plan, int32_t n_text, int32_t n_img,
+                                                       const int32_t* window, void* stream) {
+    return guarded(p, [&]() {
+        return joint_attention_impl(p, q, k, v, out, cache, head_plan, n_text, n_img, window, stream, false, residual, true);
+    });
+}
+
+extern "C" difa_status_t difa_residual_store(difa_plan_t* p, const void* o_full, const void* o_arrow, void* residual,
+                                             int32_t n_tokens, void* stream_v) {
+    return guarded(p, [&]() -> difa_status_t {
+        if (!p) return DIFA_ERR_INVALID_ARG;
+        if (!o_full || !o_arrow || !residual) return fail(p, DIFA_ERR_INVALID_ARG, "o_full, o_arrow and residual must not be NULL");
+        if (residual == o_full || residual == o_arrow) return fail(p, DIFA_ERR_INVALID_ARG, "residual must not alias an input");
+        if (n_tokens < 1 || n_tokens > p->desc.max_tokens)
+            return fail(p, DIFA_ERR_INVALID_ARG, "n_tokens must be in [1, max_tokens]");
+        if ((((uintptr_t)o_full | (uintptr_t)o_arrow | (uintptr_t)residual) & 15) != 0)
+            return fail(p, DIFA_ERR_INVALID_ARG, "o_full, o_arrow and residual must be 16-byte aligned");
+        DeviceGuard guard;
+        hipError_t e = guard.enter(p->desc.device);
+        if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("hipSetDevice", e));
+        const int64_t n = (int64_t)p->desc.batch * p->desc.heads * n_tokens * p->desc.head_dim;
+        e = difa::launch_residual_store(o_full, o_arrow, residual, n, p->desc.dtype, (hipStream_t)stream_v);
+        if (e != hipSuccess) return fail(p, DIFA_ERR_HIP, hip_msg("residual-store launch", e));
+        return DIFA_OK;
+    });
 }
 
 // Influence[h] = RSE(O[h], O'[h]) of Alg. 1 (Sec. 3.4.1, Eq. 1): one streaming pass over both tensors.

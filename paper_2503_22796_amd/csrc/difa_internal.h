@@ -24,6 +24,7 @@ struct AttnArgs {
     float* part_o;                  // device scratch: [slot][kBM][head_dim] unnormalised accumulators
     float* part_ml;                 // device scratch: [slot][kBM][2] row reference (log2 domain), row sum
     int32_t* tickets;               // device, one per cut record, zero between launches: pieces finished so far
+    const void* residual;           // device, shaped like out: kept differences of the residual-sharing heads (or NULL)
     // cached heads (bf16 kernel): out[b, h] = copy_src[b, h] for the heads listed in copy_heads
     const void* copy_src;
     const int32_t* copy_heads;      // device, n_copy entries
@@ -65,6 +66,8 @@ hipError_t launch_attn_bf16(const AttnArgs& a, int head_dim, int n_wg, hipStream
 hipError_t launch_attn_f32(const AttnArgs& a, int head_dim, int n_items, hipStream_t stream);
 hipError_t launch_cache_copy(const CopyArgs& a, hipStream_t stream);
 hipError_t launch_head_rse(const RseArgs& a, int dtype, hipStream_t stream);
+hipError_t launch_residual_store(const void* o_full, const void* o_arrow, void* residual, int64_t n_elems, int dtype,
+                                 hipStream_t stream);
 
 // File-scope device scratch of difa_joint_attention_static (defined beside the kernels that use it).
 // static_scratch_init: looks up the array's address on `device`, which must be the current device; once per

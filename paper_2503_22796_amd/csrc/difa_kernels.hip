@@ -322,6 +322,7 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
     it.merge_idx = __builtin_amdgcn_readfirstlane(seg_next.merge_idx);
     it.n_parts = __builtin_amdgcn_readfirstlane(seg_next.n_parts);
     it.first_slot = __builtin_amdgcn_readfirstlane(seg_next.first_slot);
+    it.flags = __builtin_amdgcn_readfirstlane(seg_next.flags);
 
     const int b = it.bh / a.heads, h = it.bh - b * a.heads;
     __bf16* __restrict__ og = (__bf16*)a.out + (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
@@ -822,8 +823,24 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
         // can track would stall the wavefront until loads return).
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-            const float inv = 1.0f / l_fin[qb];
-            __bf16* orow = og + (int64_t)(i_raw[qb] < N ? i_raw[qb] : N - 1) * a.stride_n;
+            float inv = 1.0f / l_fin[qb];
+            const int64_t row_off = (int64_t)(i_raw[qb] < N ? i_raw[qb] : N - 1) * a.stride_n;
+            __bf16* orow = og + row_off;
+            if (it.flags & DIFA_ITEM_ADD_RESIDUAL) {
+                // arrow attention with residual sharing: the head's kept difference is added to the
+                // normalised result before it is rounded (the lane's features: four in a row per (db, g))
+                const __bf16* rrow = (const __bf16*)cold_args()->residual + (og - (__bf16*)a.out) + row_off;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const bf16x4 rv = *(const bf16x4*)(rrow + 32 * db + 8 * g + 4 * half);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            o[db][qb][4 * g + e] = fmaf(o[db][qb][4 * g + e], inv, (float)rv[e]);
+                    }
+                inv = 1.0f;
+            }
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -1008,7 +1025,11 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a) {
         for (int d = 0; d < D; ++d) {
             const float tot = wave_sum(acc[d]);
             if ((d & 63) == lane) mine = tot / l;
-            if ((d & 63) == 63) og[(int64_t)i * a.stride_n + (d - 63) + lane] = mine;
+            if ((d & 63) == 63) {
+                const int64_t e = (int64_t)i * a.stride_n + (d - 63) + lane;
+                if (it.flags & DIFA_ITEM_ADD_RESIDUAL) mine += ((const float*)a.residual)[base + e];   // + kept difference
+                og[e] = mine;
+            }
         }
     }
 }
@@ -1058,6 +1079,40 @@ __global__ __launch_bounds__(256) void cache_copy_kernel(CopyArgs c) {
         const int64_t o0 = offset_of(idx);
         *(uint4*)(dst + o0) = *(const uint4*)(src + o0);
     }
+}
+
+// ------------------------------------------------------------------------------------------
+// Residual sharing, refresh step: residual = o_full - o_arrow, element by element, rounded once to the
+// element type.  HBM bound: three tensors pass once.
+// ------------------------------------------------------------------------------------------
+template <bool BF16>
+__global__ __launch_bounds__(256) void residual_store_kernel(const void* o_full, const void* o_arrow, void* residual,
+                                                              int64_t n_vec) {
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n_vec; i += stride) {
+        if (BF16) {
+            const bf16x8 a = ((const bf16x8*)o_full)[i], b = ((const bf16x8*)o_arrow)[i];
+            bf16x8 r;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) r[e] = (__bf16)((float)a[e] - (float)b[e]);   // the difference of two bf16 values is exact in fp32
+            ((bf16x8*)residual)[i] = r;
+        } else {
+            const floatx4 a = ((const floatx4*)o_full)[i], b = ((const floatx4*)o_arrow)[i];
+            ((floatx4*)residual)[i] = a - b;
+        }
+    }
+}
+
+hipError_t launch_residual_store(const void* o_full, const void* o_arrow, void* residual, int64_t n_elems, int dtype,
+                                 hipStream_t stream) {
+    if (n_elems <= 0) return hipSuccess;
+    const bool bf16 = dtype == DIFA_DTYPE_BF16;
+    const int64_t n_vec = n_elems / (bf16 ? 8 : 4);          // (head_dim is a multiple of 64: no remainder)
+    int64_t blocks = (n_vec + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    if (bf16) hipLaunchKernelGGL(residual_store_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream, o_full, o_arrow, residual, n_vec);
+    else hipLaunchKernelGGL(residual_store_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, o_full, o_arrow, residual, n_vec);
+    return hipGetLastError();
 }
 
 hipError_t launch_cache_copy(const CopyArgs& c, hipStream_t stream) {

@@ -88,9 +88,9 @@ difa_status_t worklist_build(int32_t batch, int32_t heads, const int32_t* head_p
     if (n64 < 1 || n64 > (int64_t)1 << 30) return DIFA_ERR_INVALID_ARG;
     for (int h = 0; h < heads; ++h) {
         const int mode = head_plan[h];
-        if (mode != DIFA_HEAD_FULL && mode != DIFA_HEAD_ARROW && mode != DIFA_HEAD_CACHE)
+        if (mode != DIFA_HEAD_FULL && mode != DIFA_HEAD_ARROW && mode != DIFA_HEAD_CACHE && mode != DIFA_HEAD_ARROW_RESIDUAL)
             return DIFA_ERR_INVALID_ARG;
-        if (mode == DIFA_HEAD_ARROW && (!window || window[h] < 0)) return DIFA_ERR_INVALID_ARG;
+        if ((mode == DIFA_HEAD_ARROW || mode == DIFA_HEAD_ARROW_RESIDUAL) && (!window || window[h] < 0)) return DIFA_ERR_INVALID_ARG;
     }
     const bool image_first = (flags & DIFA_FLAG_IMAGE_FIRST) != 0 && n_text > 0 && n_img > 0;
     const int n_kv_tiles = (int)((n64 + bn - 1) / bn);
@@ -127,6 +127,7 @@ difa_status_t worklist_build(int32_t batch, int32_t heads, const int32_t* head_p
                 r.bh = b * heads + h;
                 r.q_tile = qt;
                 r.window = w;
+                r.flags = mode == DIFA_HEAD_ARROW_RESIDUAL ? DIFA_ITEM_ADD_RESIDUAL : 0;   // arrow attention, then + r
                 if (full && !image_first) {
                     r.kv0_end = n_kv_tiles;
                     r.kv1_begin = r.kv1_end = n_kv_tiles;
@@ -282,6 +283,7 @@ difa_segment_t whole_segment(const difa_work_item_t& r) {
     s.kv1_begin = r.kv1_begin; s.kv1_end = r.kv1_end;
     s.nm1_begin = r.nm1_begin; s.nm1_end = r.nm1_end;
     s.window = r.window;
+    s.flags = r.flags;
     s.pos_begin = 0; s.pos_end = r.n_tiles;
     s.part_slot = -1;
     s.merge_idx = -1;

@@ -123,13 +123,25 @@ def test_flux_2k_shape_tile_counts():
 
 
 def test_invalid_plans_are_rejected():
-    for hp, win in (([3], [0]), ([ARROW], [-1]), ([-1], [0])):
+    for hp, win in (([4], [0]), ([ARROW], [-1]), ([3], [-1]), ([-1], [0])):
         st, _, _ = B.difa_worklist_build(1, 1, hp, win, 4, 4, 8, 4)
         assert st == B.DIFA_ERR_INVALID_ARG
     st, _, _ = B.difa_worklist_build(1, 1, [ARROW], None, 4, 4, 8, 4)
     assert st == B.DIFA_ERR_INVALID_ARG
     st, _, _ = B.difa_worklist_build(1, 1, [FULL], [0], 0, 0, 8, 4)
     assert st == B.DIFA_ERR_INVALID_ARG
+
+
+def test_residual_sharing_heads_get_the_records_of_arrow_heads_with_the_flag():
+    args = (2, 3, 37, 300, 256, 64)
+    st, plain, _ = B.difa_worklist_build(args[0], args[1], [FULL, ARROW, ARROW], [0, 17, 90], *args[2:])
+    st2, res, _ = B.difa_worklist_build(args[0], args[1], [FULL, B.DIFA_HEAD_ARROW_RESIDUAL, ARROW], [0, 17, 90], *args[2:])
+    assert st == B.DIFA_OK and st2 == B.DIFA_OK and len(plain) == len(res)
+    names = [n for n in plain.dtype.names if n != "flags"]
+    for a, b in zip(plain, res):
+        assert all(a[n] == b[n] for n in names)
+        assert a["flags"] == 0
+        assert b["flags"] == (B.DIFA_ITEM_ADD_RESIDUAL if b["bh"] % 3 == 1 else 0)
 
 
 # ----------------------------------------------------------------------------- the schedule
