@@ -163,6 +163,33 @@ def flux_2k_single_mode(mode: int, w: int = 0) -> Workload:
     return wl
 
 
+def sd3_2k() -> Workload:
+    """SD3-like 2048^2 layer: the 1K layer's heads and text length on a 128 x 128 latent."""
+    hp, win = shuffled_plan(24, [(FULL, 0, 8), (ARROW, 512, 3), (ARROW, 1024, 3), (ARROW, 2048, 2),
+                                 (CACHE, 0, 8)], seed=6)
+    return Workload("sd3_2k", 2, 24, 64, 333, 16384, hp, win, seed=6,
+                    notes="SD3-medium-like 2048^2 layer, CFG pair")
+
+
+def flux_1k_text(n_text: int) -> Workload:
+    """The FLUX-like 1024^2 layer with another prompt length (77, 154 and 256 are common encoder limits)."""
+    wl = flux_1k()
+    wl.name = f"flux_1k_text{n_text}"
+    wl.n_text = int(n_text)
+    wl.seed = 30 + int(n_text)
+    return wl
+
+
+def video_like() -> Workload:
+    """A video MMDiT layer (Sec. 2.1 names CogVideoX, HunyuanVideo and Mochi-1 as MMDiT models): a latent of
+    13 frames of 30 x 52 tokens flattened frame by frame, 256 text tokens, 24 heads of 128.  Windows are a
+    fraction of a frame, one frame and two frames (a frame is 1560 tokens)."""
+    hp, win = shuffled_plan(24, [(FULL, 0, 4), (ARROW, 520, 5), (ARROW, 1560, 5), (ARROW, 3120, 4),
+                                 (CACHE, 0, 6)], seed=7)
+    return Workload("video_like", 1, 24, 128, 256, 13 * 30 * 52, hp, win, seed=7, grid=(13, 30, 52),
+                    notes="video MMDiT-like layer, 13 x 30 x 52 latent")
+
+
 def schedule_plans(layers: int, steps: int, H: int = 24, seed: int = 5):
     """Per-(layer, step, head) plan: step 0 all full, cache only after step 0.
 
@@ -186,6 +213,9 @@ def schedule_plans(layers: int, steps: int, H: int = 24, seed: int = 5):
 CONFIGS = {
     "tiny": tiny, "sd3_1k": sd3_1k, "flux_1k": flux_1k,
     "flux_2k_mixed": flux_2k_mixed, "flux_2k_full": flux_2k_full,
+    "sd3_2k": sd3_2k, "video_like": video_like,
+    "flux_1k_text77": lambda: flux_1k_text(77), "flux_1k_text154": lambda: flux_1k_text(154),
+    "flux_1k_text256": lambda: flux_1k_text(256),
 }
 
 

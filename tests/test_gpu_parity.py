@@ -18,14 +18,14 @@ def small_workload(B, H, D, n_text, n_img, modes, wins, seed, positional=False):
                       seed=seed, positional=positional)
 
 
-def run_case(wl, dtype=torch.bfloat16, layout="bhnd", rows=None, scale=0.0, tol=None):
+def run_case(wl, dtype=torch.bfloat16, layout="bhnd", rows=None, scale=0.0, tol=None, flat_below=None):
     q, k, v = W.make_qkv(wl, dtype=dtype)
     cache = W.make_cache(wl, dtype=dtype) if (wl.head_plan == CACHE).any() else None
     out = gpu_joint_attention(q, k, v, cache, wl.head_plan, wl.window, wl.n_text, wl.n_img, scale=scale,
                               layout=layout)
     tol = tol if tol is not None else (TOL_BF16 if dtype == torch.bfloat16 else TOL_F32)
     err = check_against_oracle(out, q, k, v, cache, wl.head_plan, wl.window, wl.n_text, wl.n_img,
-                               scale=(scale if scale > 0 else None), rows=rows, tol=tol)
+                               scale=(scale if scale > 0 else None), rows=rows, tol=tol, flat_below=flat_below)
     print(f"{wl.name}: dtype={dtype} layout={layout} max_abs_err={err:.3e} max|out|={float(out.float().abs().max()):.2f} "
           f"so far: worst excess over 2^-7|ref| {getattr(check_against_oracle, 'worst_excess', float('nan')):.3e}, "
           f"worst rms error / rms bar {getattr(check_against_oracle, 'worst_rms', float('nan')):.3f}", flush=True)
@@ -59,6 +59,24 @@ def test_flux_2k_full_all_rows():
 
 def test_flux_2k_arrow_w128_all_rows():
     run_case(W.flux_2k_single_mode(ARROW, 128))
+
+
+# ----------------------------------------------------------------------------- further layer shapes
+@pytest.mark.parametrize("n_text", [77, 154, 256])
+def test_flux_1k_other_prompt_lengths_all_rows(n_text):
+    run_case(W.flux_1k_text(n_text), flat_below=4.0)
+
+
+def test_sd3_2k_sampled_rows():
+    wl = W.sd3_2k()
+    rows = boundary_rows(wl.n_text, wl.n_img, wl.window[wl.head_plan == ARROW], extra=96, seed=6)
+    run_case(wl, rows=rows, flat_below=4.0)
+
+
+def test_video_like_layer_sampled_rows():
+    wl = W.video_like()       # 13 x 30 x 52 latent: not a square grid, N = 20 536 is not a multiple of the tile sizes
+    rows = boundary_rows(wl.n_text, wl.n_img, wl.window[wl.head_plan == ARROW], extra=96, seed=7)
+    run_case(wl, rows=rows, flat_below=4.0)
 
 
 # ----------------------------------------------------------------------------- shapes and edges

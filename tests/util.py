@@ -54,8 +54,13 @@ def gpu_joint_attention(q, k, v, cache, head_plan, window, n_text, n_img, scale=
 
 
 def check_against_oracle(out, q, k, v, cache, head_plan, window, n_text, n_img, scale=None, rows=None,
-                         tol=TOL_BF16, block=None, image_first=False):
-    """Element-by-element comparison; returns the max abs error over computed heads."""
+                         tol=TOL_BF16, block=None, image_first=False, flat_below=None):
+    """Element-by-element comparison; returns the max abs error over computed heads.
+
+    flat_below: None applies the flat bar `tol` to every element (the named configurations).  A number applies
+    it to the elements whose reference is smaller than that in magnitude and leaves the larger ones to the
+    magnitude-aware bar: from |ref| = 4 on, half a step of the bf16 output alone is 0.0156, and the rounding
+    of the weights adds up to 1e-2 on top, so whether such an element stays under 2e-2 is a matter of the draw."""
     from oracle import difa_oracle as O
     ref, ref_raw, _ = O.joint_attention(q, k, v, cache, head_plan, window, n_text, n_img,
                                         scale=scale, rows=rows, block=block, image_first=image_first)
@@ -72,7 +77,8 @@ def check_against_oracle(out, q, k, v, cache, head_plan, window, n_text, n_img, 
             assert torch.isfinite(g).all(), f"head {h}: non-finite output (unwritten or NaN rows)"
             diff = (g - ref[:, h]).abs()
             err = float(diff.max())
-            assert err <= tol, f"head {h} (mode {hp[h]}, w {window[h]}): max abs err {err:.3e} > {tol}"
+            flat = diff if flat_below is None else torch.where(ref[:, h].abs() < flat_below, diff, torch.zeros_like(diff))
+            assert float(flat.max()) <= tol, f"head {h} (mode {hp[h]}, w {window[h]}): max abs err {float(flat.max()):.3e} > {tol}"
             if got.dtype == torch.bfloat16 and tol == TOL_BF16:
                 excess = float((diff - REL_BF16 * ref[:, h].abs()).max())
                 assert excess <= ABS_BF16, \
