@@ -339,6 +339,8 @@ DiePlan deal_and_cut(const std::vector<difa_work_item_t>& q, int per_die, int64_
     // wide_rooms: the pooled records are laid end to end and poured into the workgroups' rooms, one workgroup
     // filled before the next (the least loaded one) is opened, so a record is cut where a room ends.
     // Otherwise every piece goes to the workgroup that is the least loaded at that moment.
+    std::vector<size_t> n_whole((size_t)per_die);
+    for (int w = 0; w < per_die; ++w) n_whole[(size_t)w] = plan.lists[(size_t)w].size();
     int cur = -1;
     auto room_of = [&](int w) { return (target - load[(size_t)w] - kSegOverhead) / kUnit; };   // in key tiles
     for (const difa_work_item_t& r : pool) {
@@ -364,6 +366,20 @@ DiePlan deal_and_cut(const std::vector<difa_work_item_t>& q, int per_die, int64_
         }
         finish_record(plan, r, pieces);
     }
+    // A poured room holds the tail of one record and the head of the next one, neighbouring query tiles of
+    // one head as a rule.  Run in the order of their first key position (the shorter one first among equals),
+    // the workgroups of the die walk through that head's K/V within a fraction of a record of each other and
+    // share the tiles in the die's L2, as they do on whole records; the pieces of a record may finish in any
+    // order, since the last one to arrive folds them.
+    if (wide_rooms)
+        for (int w = 0; w < per_die; ++w) {
+            auto& l = plan.lists[(size_t)w];
+            std::stable_sort(l.begin() + (std::ptrdiff_t)n_whole[(size_t)w], l.end(),
+                             [](const difa_segment_t& a, const difa_segment_t& b) {
+                                 return a.pos_begin != b.pos_begin ? a.pos_begin < b.pos_begin
+                                                                   : a.pos_end - a.pos_begin < b.pos_end - b.pos_begin;
+                             });
+        }
     plan.makespan = *std::max_element(load.begin(), load.end());
     return plan;
 }
