@@ -385,7 +385,7 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
     // Element mask of one 32-key block whose first key is j0.  The host marks a tile as masked when any
     // of the workgroup's 256 rows has a forbidden key in it; for the rows of one wavefront most such
     // blocks lie entirely inside the band, or are cut by one band edge only.  That is decided here from
-    // scalars, so that the common cases cost nothing or one compare per score.
+    // scalars, so that the common cases cost nothing or two plain integer instructions per score.
     const int row_first = it.q_tile * kBM + (int)wave_u * RW;              // this wavefront's rows (uniform)
     const int row_last = row_first + RW - 1 < N - 1 ? row_first + RW - 1 : N - 1;
     auto mask_block = [&](int j0, floatx16 (&s)[QB]) {
@@ -395,39 +395,39 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
             const bool low = row_last - it.window > j0;                    // some row's band starts after j0
             const bool high = row_first + it.window < j0 + 31;             // some row's band ends before the block does
             if (!low && !high) return;
-            // key offset inside the block (8*(r/4) + r%4, a constant per register) against the row's edge
-            // (compare and select written out so that the scores are replaced where they are, two
-            // instructions per score; the wait states are what a vector write of VCC needs before a
-            // vector instruction reads it)
-            const float ninf = -INFINITY;
-            if (low && !high) {
+            // Register r of a lane holds the key at offset 8*(r/4) + r%4 (+ 4*half) of the block, increasing
+            // with r, so the keys below the band's start are the lane's first k registers and the keys beyond
+            // its end the last ones.  The count k comes from the lane's edge with a handful of integer
+            // instructions; bit r of `gone` says that register r is to be replaced, and each score then costs a
+            // signed one-bit extract (all ones or zero) and a bit-select between the score and -inf.  No
+            // compare writes a lane mask that the next instruction would have to wait for (a compare and a
+            // select that reads its result cost 20 clocks a pair on this chip, four ordinary instructions 16).
+            auto below = [](int e) {                                        // registers whose key offset is < e
+                const int ec = e < 0 ? 0 : (e > 32 ? 32 : e);
+                const int rem = ec & 7;
+                return 4 * (ec >> 3) + (rem < 4 ? rem : 4);
+            };
+            const unsigned ninf = 0xff800000u;
 #pragma unroll
-                for (int qb = 0; qb < QB; ++qb) {
-                    const int edge = rs[qb].lo - j0 - 4 * half;
+            for (int qb = 0; qb < QB; ++qb) {
+                unsigned gone = 0;
+                if (low) gone = (1u << below(rs[qb].lo - j0 - 4 * half)) - 1u;
+                if (high) gone |= ~((1u << below(rs[qb].lo + (int)rs[qb].span - j0 - 4 * half + 1)) - 1u);
+                // (one statement for the block's sixteen scores, written out so that the compiler neither turns
+                // the bit-select back into a compare and a select nor pads every score with a wait state)
+                float x[16];
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        float x = s[qb][r];
-                        asm volatile("v_cmp_gt_i32 vcc, %1, %2\n\ts_nop 1\n\tv_cndmask_b32 %0, %0, %3, vcc"
-                                     : "+v"(x) : "v"(edge), "n"(8 * (r >> 2) + (r & 3)), "v"(ninf) : "vcc");
-                        s[qb][r] = x;
-                    }
-                }
-                return;
+                for (int r = 0; r < 16; ++r) x[r] = s[qb][r];
+                unsigned t0, t1;
+                asm volatile("v_bfe_i32 %16, %18, 0, 1\n\tv_bfe_i32 %17, %18, 1, 1\n\tv_bfi_b32 %0, %16, %19, %0\n\tv_bfi_b32 %1, %17, %19, %1\n\tv_bfe_i32 %16, %18, 2, 1\n\tv_bfe_i32 %17, %18, 3, 1\n\tv_bfi_b32 %2, %16, %19, %2\n\tv_bfi_b32 %3, %17, %19, %3\n\tv_bfe_i32 %16, %18, 4, 1\n\tv_bfe_i32 %17, %18, 5, 1\n\tv_bfi_b32 %4, %16, %19, %4\n\tv_bfi_b32 %5, %17, %19, %5\n\tv_bfe_i32 %16, %18, 6, 1\n\tv_bfe_i32 %17, %18, 7, 1\n\tv_bfi_b32 %6, %16, %19, %6\n\tv_bfi_b32 %7, %17, %19, %7\n\tv_bfe_i32 %16, %18, 8, 1\n\tv_bfe_i32 %17, %18, 9, 1\n\tv_bfi_b32 %8, %16, %19, %8\n\tv_bfi_b32 %9, %17, %19, %9\n\tv_bfe_i32 %16, %18, 10, 1\n\tv_bfe_i32 %17, %18, 11, 1\n\tv_bfi_b32 %10, %16, %19, %10\n\tv_bfi_b32 %11, %17, %19, %11\n\tv_bfe_i32 %16, %18, 12, 1\n\tv_bfe_i32 %17, %18, 13, 1\n\tv_bfi_b32 %12, %16, %19, %12\n\tv_bfi_b32 %13, %17, %19, %13\n\tv_bfe_i32 %16, %18, 14, 1\n\tv_bfe_i32 %17, %18, 15, 1\n\tv_bfi_b32 %14, %16, %19, %14\n\tv_bfi_b32 %15, %17, %19, %15"
+                             : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]),
+                               "+v"(x[8]), "+v"(x[9]), "+v"(x[10]), "+v"(x[11]), "+v"(x[12]), "+v"(x[13]), "+v"(x[14]), "+v"(x[15]),
+                               "=&v"(t0), "=&v"(t1)
+                             : "v"(gone), "v"(ninf));
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[qb][r] = x[r];
             }
-            if (high && !low) {
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb) {
-                    const int edge = rs[qb].lo + (int)rs[qb].span - j0 - 4 * half;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        float x = s[qb][r];
-                        asm volatile("v_cmp_lt_i32 vcc, %1, %2\n\ts_nop 1\n\tv_cndmask_b32 %0, %0, %3, vcc"
-                                     : "+v"(x) : "v"(edge), "n"(8 * (r >> 2) + (r & 3)), "v"(ninf) : "vcc");
-                        s[qb][r] = x;
-                    }
-                }
-                return;
-            }
+            return;
         }
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)

@@ -242,21 +242,30 @@ extern "C" difa_status_t difa_worklist_build(int32_t batch, int32_t heads, const
 // The hardware dispatcher would hand whole records to compute units as they free up; with records
 // of a few hundred key tiles each, the last round leaves most of the chip idle (1584 equal records on
 // 256 compute units: 6.19 rounds cost 7).  Here the distribution is computed on the host instead:
-// whole records are dealt out in order to the least loaded workgroup of their die (which keeps the
-// workgroups of a die on neighbouring query tiles of one head, marching through its K/V together),
-// and the records that no longer fit under the die's average load are cut along their key-tile
-// positions into pieces that fill the workgroups up to that average.
+// whole records are dealt out, costliest first, to the least loaded workgroup of their die (which keeps
+// the workgroups of a die on neighbouring query tiles of one head, marching through its K/V together),
+// and the records that no longer fit under a target load are cut along their key-tile positions into
+// pieces that fill the workgroups up to it.  The target is found by a few dry runs (a cut costs a
+// good part of a short record, so how much load there is depends on how much is cut); for layers of few,
+// long records, filling the workgroups one after the other, or not cutting at all, is tried as well, and
+// the plan with the earliest predicted finish is kept.
 // ------------------------------------------------------------------------------------------
 namespace {
 
-// Cost model of a segment, in quarter key-tile iterations (measured on MI355X: a plain iteration takes
-// about 3700 clocks, one on a masked tile up to 5500 -- per-workgroup fits put it at 0.7-0.9 extra
-// iterations --, and the fixed cost of a segment -- first tiles, a slower first iteration, drain,
-// epilogue -- at about four iterations; a sweep of both constants over the named layers agrees).
-constexpr int kUnit = 4;                  // cost units per key-tile iteration
-constexpr int kMaskedExtra = 3;           // extra units of an iteration on a masked tile
-constexpr int kSegOverhead = 4 * kUnit;   // starting and finishing a segment
-constexpr int kMinPiece = 8;              // shortest piece (in key tiles) worth cutting off a record
+// Cost model of a segment, in eighths of a plain key-tile iteration.  Fitted on MI355X from clock counters
+// around the kernel's phases, regressed per workgroup on what the schedule had given it (head_dim 128 and
+// 64, the 1K and 2K layers): a plain iteration takes about 3000 clocks (2300 at head_dim 64), one on a tile
+// that needs the element mask 0.8-1.0 iterations more; starting and finishing a whole record costs 4-5
+// iterations; a piece of a cut record 7-12 (its partial result goes to scratch and a ticket is drawn, both
+// round trips to memory), and the piece that arrives last pays 3-9 more per other piece it folds in.  Who
+// arrives last is not known here, so every piece is charged its share.
+constexpr int kUnit = 8;                  // cost units per key-tile iteration
+constexpr int kMaskedExtra = 7;           // extra units of an iteration on a masked tile
+constexpr int kWholeOverhead = 36;        // starting and finishing a whole record
+constexpr int kPieceOverhead = 72;        // ... a piece of a cut record, without the fold
+constexpr int kFoldPerSlot = 40;          // folding one other piece's partial result in
+constexpr int kPieceExpected = kPieceOverhead + kFoldPerSlot / 2;   // what a piece is charged while cutting
+constexpr int kMinPiece = 12;             // shortest piece (in key tiles) worth cutting off a record
 
 // Masked tiles among positions [p0, p1) of a record's visiting order.
 int masked_between(const difa_work_item_t& r, int p0, int p1) {
@@ -272,9 +281,10 @@ int masked_between(const difa_work_item_t& r, int p0, int p1) {
     return n;
 }
 
-int64_t range_cost(const difa_work_item_t& r, int p0, int p1) {
-    return (int64_t)kUnit * (p1 - p0) + (int64_t)kMaskedExtra * masked_between(r, p0, p1) + kSegOverhead;
+int64_t tiles_cost(const difa_work_item_t& r, int p0, int p1) {
+    return (int64_t)kUnit * (p1 - p0) + (int64_t)kMaskedExtra * masked_between(r, p0, p1);
 }
+int64_t whole_cost(const difa_work_item_t& r) { return tiles_cost(r, 0, r.n_tiles) + kWholeOverhead; }
 
 difa_segment_t whole_segment(const difa_work_item_t& r) {
     difa_segment_t s{};
@@ -292,86 +302,114 @@ difa_segment_t whole_segment(const difa_work_item_t& r) {
     return s;
 }
 
-// One die's share of the schedule: a segment list per workgroup, slots numbered from 0.
+// One die's share of the schedule.  A dry run fills in the loads and counts only.
 struct DiePlan {
-    std::vector<std::vector<difa_segment_t>> lists;
+    std::vector<std::vector<difa_segment_t>> lists;   // a segment list per workgroup, slots numbered from 0
     std::vector<difa_merge_item_t> merges;
+    std::vector<int64_t> load;
     int n_slots = 0;
-    int64_t makespan = 0;
+    int most_parts = 1;
+    int64_t makespan = 0, total = 0;
 };
 
-void finish_record(DiePlan& plan, const difa_work_item_t& r, std::vector<std::pair<int, difa_segment_t>>& pieces) {
-    if (pieces.size() > 1) {
-        difa_merge_item_t m{r.bh, r.q_tile, plan.n_slots, (int32_t)pieces.size()};
-        for (auto& pc : pieces) {
-            pc.second.first_slot = m.first_slot;
-            pc.second.part_slot = plan.n_slots++;
-            pc.second.merge_idx = (int32_t)plan.merges.size();
-            pc.second.n_parts = (int32_t)pieces.size();
-        }
-        plan.merges.push_back(m);
+struct Piece { int wg, pos_begin, pos_end; };
+
+void finish_record(DiePlan& plan, const difa_work_item_t& r, const std::vector<Piece>& pieces, bool dry) {
+    const int n = (int)pieces.size();
+    plan.most_parts = std::max(plan.most_parts, n);
+    if (n > 1) {
+        // the pieces were charged kPieceExpected each; put the fold at what this record's piece count makes it
+        const int64_t fold = (int64_t)kFoldPerSlot * (n - 1) / n - kFoldPerSlot / 2;
+        for (const Piece& pc : pieces) plan.load[(size_t)pc.wg] += fold;
     }
-    for (auto& pc : pieces) plan.lists[(size_t)pc.first].push_back(pc.second);
+    if (dry) {
+        if (n > 1) plan.n_slots += n;
+        return;
+    }
+    const int first_slot = plan.n_slots;
+    for (const Piece& pc : pieces) {
+        difa_segment_t s = whole_segment(r);
+        s.pos_begin = pc.pos_begin;
+        s.pos_end = pc.pos_end;
+        if (n > 1) {
+            s.first_slot = first_slot;
+            s.part_slot = plan.n_slots++;
+            s.merge_idx = (int32_t)plan.merges.size();
+            s.n_parts = n;
+        }
+        plan.lists[(size_t)pc.wg].push_back(s);
+    }
+    if (n > 1) plan.merges.push_back(difa_merge_item_t{r.bh, r.q_tile, first_slot, n});
 }
 
-// Whole records dealt in order to the least loaded workgroup (neighbouring query tiles of a head run side
-// by side and share its K/V tiles in the die's L2); the records that no longer fit under the target are cut
-// into pieces that fill the workgroups up to it.
-DiePlan deal_and_cut(const std::vector<difa_work_item_t>& q, int per_die, int64_t target, int slot_budget, bool wide_rooms) {
+void close_plan(DiePlan& plan) {
+    plan.makespan = *std::max_element(plan.load.begin(), plan.load.end());
+    plan.total = 0;
+    for (int64_t l : plan.load) plan.total += l;
+}
+
+// Records in order of decreasing cost.  A record goes whole to the least loaded workgroup (so neighbouring
+// query tiles of a head run side by side and share its K/V tiles in the die's L2) as long as that leaves the
+// workgroup room for another half of it; otherwise it is poured: laid into the room of the workgroup that is
+// being filled, cut where that room ends, the rest into the room of the workgroup that is then the least
+// loaded, and so on.  Rooms are therefore of the order of a record when long records are cut (two or three
+// pieces each, so the workgroup that folds them together at the end reads one or two slots, not ten), and
+// short records, which are not worth cutting, fill the gaps that remain.
+DiePlan deal_and_pour(const std::vector<difa_work_item_t>& q, const std::vector<int64_t>& cost, int per_die,
+                      int64_t target, int slot_budget, bool dry) {
     DiePlan plan;
-    plan.lists.resize((size_t)per_die);
-    std::vector<int64_t> load((size_t)per_die, 0);
+    if (!dry) plan.lists.resize((size_t)per_die);
+    plan.load.assign((size_t)per_die, 0);
+    std::vector<int64_t>& load = plan.load;
     auto least = [&]() { return (int)(std::min_element(load.begin(), load.end()) - load.begin()); };
-    std::vector<difa_work_item_t> pool;
-    for (const difa_work_item_t& r : q) {
-        const int w = least();
-        const int64_t c = range_cost(r, 0, r.n_tiles);
-        // wide_rooms: a workgroup stops taking whole records while it still has room for half a record or
-        // more.  The rooms that the pieces fill are then of the order of a record, a cut record has two or
-        // three pieces, and the workgroup that folds them together at the end reads one or two slots, not ten.
-        if (load[(size_t)w] + c + (wide_rooms ? c / 2 : 0) <= target) {
-            plan.lists[(size_t)w].push_back(whole_segment(r));
-            load[(size_t)w] += c;
-        } else {
-            pool.push_back(r);
-        }
-    }
-    // wide_rooms: the pooled records are laid end to end and poured into the workgroups' rooms, one workgroup
-    // filled before the next (the least loaded one) is opened, so a record is cut where a room ends.
-    // Otherwise every piece goes to the workgroup that is the least loaded at that moment.
-    std::vector<size_t> n_whole((size_t)per_die);
-    for (int w = 0; w < per_die; ++w) n_whole[(size_t)w] = plan.lists[(size_t)w].size();
+    std::vector<Piece> pieces;
+    std::vector<size_t> n_whole((size_t)per_die, 0);
+    std::vector<char> poured((size_t)per_die, 0);
     int cur = -1;
-    auto room_of = [&](int w) { return (target - load[(size_t)w] - kSegOverhead) / kUnit; };   // in key tiles
-    for (const difa_work_item_t& r : pool) {
-        std::vector<std::pair<int, difa_segment_t>> pieces;
+    auto room_of = [&](int w) { return (target - load[(size_t)w] - kPieceExpected) / kUnit; };   // in key tiles
+    for (size_t i = 0; i < q.size(); ++i) {
+        const difa_work_item_t& r = q[i];
+        const int64_t c = cost[i];
+        const int lw = least();
+        if (load[(size_t)lw] + c + c / 2 <= target) {
+            load[(size_t)lw] += c;
+            if (!dry) plan.lists[(size_t)lw].push_back(whole_segment(r));
+            if (!poured[(size_t)lw]) ++n_whole[(size_t)lw];
+            continue;
+        }
+        pieces.clear();
         int pos = 0;
         while (pos < r.n_tiles) {
-            if (!wide_rooms || cur < 0 || room_of(cur) < kMinPiece) cur = least();
+            if (cur < 0 || room_of(cur) < kMinPiece) cur = least();
             const int w = cur;
             const int remaining = r.n_tiles - pos;
             const int64_t room = room_of(w);
             int take = remaining;
             const bool may_cut = plan.n_slots + (int)pieces.size() + 2 <= slot_budget;
-            if (may_cut && room >= kMinPiece && room < remaining) {
+            if (pos == 0 && load[(size_t)w] + c <= target) {
+                // the whole record fits
+            } else if (may_cut && room >= kMinPiece && room < remaining) {
                 take = (int)room;
-                if (remaining - take < kMinPiece) take = remaining;
+                if (remaining - take < kMinPiece) take = remaining - kMinPiece >= kMinPiece ? remaining - kMinPiece : remaining;
+            } else if (may_cut && room < kMinPiece && remaining >= 4 * kMinPiece) {
+                // no room anywhere (the target was too low): spread what is left over the least loaded
+                // workgroups in pieces of two to four times the shortest one, rather than on one of them
+                const int n = (remaining + 3 * kMinPiece - 1) / (3 * kMinPiece);
+                take = (remaining + n - 1) / n;
             }
-            difa_segment_t s = whole_segment(r);
-            s.pos_begin = pos;
-            s.pos_end = pos + take;
-            pieces.push_back({w, s});
-            load[(size_t)w] += range_cost(r, pos, pos + take);
+            pieces.push_back(Piece{w, pos, pos + take});
+            load[(size_t)w] += tiles_cost(r, pos, pos + take) + (take == r.n_tiles ? kWholeOverhead : kPieceExpected);
+            poured[(size_t)w] = 1;
             pos += take;
         }
-        finish_record(plan, r, pieces);
+        finish_record(plan, r, pieces, dry);
     }
     // A poured room holds the tail of one record and the head of the next one, neighbouring query tiles of
     // one head as a rule.  Run in the order of their first key position (the shorter one first among equals),
     // the workgroups of the die walk through that head's K/V within a fraction of a record of each other and
     // share the tiles in the die's L2, as they do on whole records; the pieces of a record may finish in any
     // order, since the last one to arrive folds them.
-    if (wide_rooms)
+    if (!dry)
         for (int w = 0; w < per_die; ++w) {
             auto& l = plan.lists[(size_t)w];
             std::stable_sort(l.begin() + (std::ptrdiff_t)n_whole[(size_t)w], l.end(),
@@ -380,51 +418,85 @@ DiePlan deal_and_cut(const std::vector<difa_work_item_t>& q, int per_die, int64_
                                                                    : a.pos_end - a.pos_begin < b.pos_end - b.pos_begin;
                              });
         }
-    plan.makespan = *std::max_element(load.begin(), load.end());
+    close_plan(plan);
     return plan;
 }
 
 // The records laid end to end and handed out in runs of the target cost: workgroup 0 is filled, then
 // workgroup 1, ...; a record that crosses a boundary is cut there.
-DiePlan fill_in_order(const std::vector<difa_work_item_t>& q, int per_die, int64_t target, int slot_budget) {
+DiePlan fill_in_order(const std::vector<difa_work_item_t>& q, const std::vector<int64_t>& cost, int per_die,
+                      int64_t target, int slot_budget, bool dry) {
     DiePlan plan;
-    plan.lists.resize((size_t)per_die);
-    std::vector<int64_t> load((size_t)per_die, 0);
+    if (!dry) plan.lists.resize((size_t)per_die);
+    plan.load.assign((size_t)per_die, 0);
+    std::vector<int64_t>& load = plan.load;
+    std::vector<Piece> pieces;
     int w = 0;
-    for (const difa_work_item_t& r : q) {
-        std::vector<std::pair<int, difa_segment_t>> pieces;
+    for (size_t i = 0; i < q.size(); ++i) {
+        const difa_work_item_t& r = q[i];
+        pieces.clear();
         int pos = 0;
+        if (w < per_die - 1 && load[(size_t)w] > 0 && load[(size_t)w] + cost[i] > target &&
+            (target - load[(size_t)w] - kPieceExpected) / kUnit < kMinPiece)
+            ++w;                                                      // no room worth a piece: the next workgroup goes on
         while (pos < r.n_tiles) {
             const int remaining = r.n_tiles - pos;
-            const int64_t room = (target - load[(size_t)w] - kSegOverhead) / kUnit;   // in key tiles
+            const int64_t ovh = pos == 0 ? kWholeOverhead : kPieceExpected;
             int take = remaining;
-            if (w < per_die - 1 && room < remaining) {
+            if (w < per_die - 1 && load[(size_t)w] + tiles_cost(r, pos, r.n_tiles) + ovh > target) {
+                const int64_t room = (target - load[(size_t)w] - kPieceExpected) / kUnit;   // in key tiles
                 const bool may_cut = plan.n_slots + (int)pieces.size() + 2 <= slot_budget;
-                if (room < kMinPiece || !may_cut) {
-                    if (load[(size_t)w] > 0) { ++w; continue; }      // this workgroup is full: the next one goes on
-                } else if (remaining - room >= kMinPiece) {
-                    take = (int)room;
-                }                                                     // else: too little would be left over, overfill
-            }
-            difa_segment_t s = whole_segment(r);
-            s.pos_begin = pos;
-            s.pos_end = pos + take;
-            pieces.push_back({w, s});
-            load[(size_t)w] += range_cost(r, pos, pos + take);
+                if (may_cut && room >= kMinPiece && remaining - room >= kMinPiece) take = (int)room;
+                else if (may_cut && room >= kMinPiece && remaining - kMinPiece >= kMinPiece) take = remaining - kMinPiece;
+                else if (load[(size_t)w] > 0 && pos == 0) { ++w; continue; }   // rather start it on the next workgroup
+            }                                                         // else: overfill
+            pieces.push_back(Piece{w, pos, pos + take});
+            load[(size_t)w] += tiles_cost(r, pos, pos + take) + (take == r.n_tiles ? kWholeOverhead : kPieceExpected);
             pos += take;
-            if (w < per_die - 1 && load[(size_t)w] + kSegOverhead + kUnit * kMinPiece > target) ++w;
+            if (pos < r.n_tiles && w < per_die - 1) ++w;              // cut: the rest starts the next workgroup
         }
-        finish_record(plan, r, pieces);
+        finish_record(plan, r, pieces, dry);
     }
-    plan.makespan = *std::max_element(load.begin(), load.end());
+    close_plan(plan);
     return plan;
 }
 
-}  // namespace
+// The smallest target a method gets along with: too low a target leaves work over that lands on one
+// workgroup, too high a one leaves the last workgroups idle.  A few dry runs, each aiming just above the mean
+// load of the one before (the mean moves little: only the number of pieces changes it).
+template <class Run>
+int64_t settle_target(int64_t first, int per_die, Run run) {
+    int64_t target = first, best_target = first, best_span = -1;
+    for (int round = 0; round < 3; ++round) {
+        const DiePlan p = run(target, true);
+        if (best_span < 0 || p.makespan < best_span) { best_span = p.makespan; best_target = target; }
+        const int64_t mean = (p.total + per_die - 1) / per_die;
+        int64_t next;
+        if (p.makespan > target + target / 128) next = target + std::max<int64_t>(kUnit, (p.makespan - target) / 8);   // work was left over
+        else next = mean + kUnit;                                    // it all went in: aim just above the mean load
+        if (next == target || (p.makespan <= target + target / 128 && next > target)) break;
+        target = next;
+    }
+    return best_target;
+}
 
-namespace {
+// Whole records only, each to the least loaded workgroup: the plan to beat when records are few and a cut
+// costs a good part of a record.
+DiePlan deal_whole(const std::vector<difa_work_item_t>& q, const std::vector<int64_t>& cost, int per_die, bool dry) {
+    DiePlan plan;
+    if (!dry) plan.lists.resize((size_t)per_die);
+    plan.load.assign((size_t)per_die, 0);
+    for (size_t i = 0; i < q.size(); ++i) {
+        const int w = (int)(std::min_element(plan.load.begin(), plan.load.end()) - plan.load.begin());
+        plan.load[(size_t)w] += cost[i];
+        if (!dry) plan.lists[(size_t)w].push_back(whole_segment(q[i]));
+    }
+    close_plan(plan);
+    return plan;
+}
+
 difa_status_t schedule_build(const difa_work_item_t* items, int32_t n_items, int32_t n_wg,
-                             int32_t n_xcd, difa_segment_t* segs, int32_t seg_capacity,
+                             int32_t n_xcd, const double* die_speed, difa_segment_t* segs, int32_t seg_capacity,
                              int32_t* wg_begin, int32_t* n_segs_out, difa_merge_item_t* merges,
                              int32_t merge_capacity, int32_t* n_merges_out, int32_t* n_slots_out) {
     if (n_items < 0 || (n_items > 0 && !items) || n_wg < 1 || n_xcd < 1 || n_wg % n_xcd != 0 || !wg_begin ||
@@ -440,28 +512,37 @@ difa_status_t schedule_build(const difa_work_item_t* items, int32_t n_items, int
     std::stable_sort(recs.begin(), recs.end(), [](const difa_work_item_t& a, const difa_work_item_t& b) {
         return a.bh != b.bh ? a.bh < b.bh : a.q_tile < b.q_tile;
     });
-    // heads in order of decreasing cost, the whole sequence cut into n_xcd runs of equal cost
+    // heads in order of decreasing cost, the whole sequence cut into n_xcd runs whose costs are in
+    // proportion to the dies' speeds (equal when none are given)
     struct HeadSpan { size_t first, count; int64_t cost; };
     std::vector<HeadSpan> spans;
     for (size_t i = 0; i < recs.size();) {
         size_t j = i;
         int64_t cost = 0;
-        while (j < recs.size() && recs[j].bh == recs[i].bh) { cost += range_cost(recs[j], 0, recs[j].n_tiles); ++j; }
+        while (j < recs.size() && recs[j].bh == recs[i].bh) { cost += whole_cost(recs[j]); ++j; }
         spans.push_back({i, j - i, cost});
         i = j;
     }
     std::stable_sort(spans.begin(), spans.end(), [](const HeadSpan& a, const HeadSpan& b) { return a.cost > b.cost; });
     int64_t total = 0;
     for (const HeadSpan& sp : spans) total += sp.cost;
+    std::vector<double> upto((size_t)n_xcd + 1, 0.0);      // cumulative share of the work that dies 0 .. x-1 take
+    {
+        double sum = 0.0;
+        for (int x = 0; x < n_xcd; ++x) sum += die_speed ? die_speed[x] : 1.0;
+        for (int x = 0; x < n_xcd; ++x) upto[(size_t)x + 1] = upto[(size_t)x] + (die_speed ? die_speed[x] : 1.0) / sum;
+        upto[(size_t)n_xcd] = 2.0;
+    }
     std::vector<std::vector<difa_work_item_t>> die((size_t)n_xcd);
     int64_t cum = 0;
+    int x_at = 0;
     for (const HeadSpan& sp : spans)
         for (size_t k = 0; k < sp.count; ++k) {
             const difa_work_item_t& r = recs[sp.first + k];
-            const int64_t c = range_cost(r, 0, r.n_tiles);
-            int64_t x = total > 0 ? ((2 * cum + c) * n_xcd) / (2 * total) : 0;
-            x = std::min<int64_t>(std::max<int64_t>(x, 0), n_xcd - 1);
-            die[(size_t)x].push_back(r);
+            const int64_t c = whole_cost(r);
+            const double mid = total > 0 ? (double)(2 * cum + c) / (double)(2 * total) : 0.0;
+            while (x_at < n_xcd - 1 && mid >= upto[(size_t)x_at + 1]) ++x_at;
+            die[(size_t)x_at].push_back(r);
             cum += c;
         }
 
@@ -469,36 +550,38 @@ difa_status_t schedule_build(const difa_work_item_t* items, int32_t n_items, int
     const int slot_capacity = 2 * n_wg;
     std::vector<std::vector<difa_segment_t>> lists((size_t)n_wg);
     std::vector<difa_merge_item_t> merge_list;
+    std::vector<int64_t> cost;
     int n_slots = 0;
     for (int x = 0; x < n_xcd; ++x) {
         std::vector<difa_work_item_t>& q = die[(size_t)x];
-        // longest records first (a query tile that holds text rows visits every key tile), in classes of
-        // 16 key tiles so that the records of one head, which differ by a tile or two, stay neighbours
-        std::stable_sort(q.begin(), q.end(), [](const difa_work_item_t& a, const difa_work_item_t& b) {
-            return a.n_tiles / 16 > b.n_tiles / 16;
-        });
-        int64_t die_cost = 0;
-        for (const difa_work_item_t& r : q) die_cost += range_cost(r, 0, r.n_tiles);
-        // every workgroup is expected to take one extra piece
-        const int64_t target = (die_cost + (int64_t)per_die * kSegOverhead + per_die - 1) / per_die;
-        const int budget = slot_capacity - n_slots - 2 * per_die * (n_xcd - 1 - x);   // this die's share of the slots
-        DiePlan dealt = deal_and_cut(q, per_die, target, budget, false);
-        // Long records on a well filled die would be cut into many short pieces, all of which one workgroup
-        // has to fold together at the very end: deal again with rooms of the order of a record.
-        int most_parts = 0;
-        for (const difa_merge_item_t& m : dealt.merges) most_parts = std::max(most_parts, (int)m.n_parts);
-        if (most_parts > 3) {
-            DiePlan wide = deal_and_cut(q, per_die, target, budget, true);
-            int wide_parts = 0;
-            for (const difa_merge_item_t& m : wide.merges) wide_parts = std::max(wide_parts, (int)m.n_parts);
-            if (wide_parts < most_parts && wide.makespan * 50 <= dealt.makespan * 51) dealt = std::move(wide);
+        // costliest records first (a query tile that holds text rows visits every key tile); the interior
+        // query tiles of a head cost the same and stay neighbours
+        {
+            std::vector<std::pair<int64_t, int>> key(q.size());
+            for (size_t i = 0; i < q.size(); ++i) key[i] = {-whole_cost(q[i]), (int)i};
+            std::sort(key.begin(), key.end());                       // (ties keep their order: the index decides)
+            std::vector<difa_work_item_t> sorted(q.size());
+            cost.resize(q.size());
+            for (size_t i = 0; i < q.size(); ++i) { sorted[i] = q[(size_t)key[i].second]; cost[i] = -key[i].first; }
+            q.swap(sorted);
         }
+        int64_t die_cost = 0;
+        for (size_t i = 0; i < q.size(); ++i) die_cost += cost[i];
+        const int budget = slot_capacity - n_slots - 2 * per_die * (n_xcd - 1 - x);   // this die's share of the slots
+        // every workgroup is expected to take one piece
+        const int64_t first = (die_cost + (int64_t)per_die * kPieceExpected + per_die - 1) / per_die;
+        auto deal = [&](int64_t t, bool dry) { return deal_and_pour(q, cost, per_die, t, budget, dry); };
+        auto fill = [&](int64_t t, bool dry) { return fill_in_order(q, cost, per_die, t, budget, dry); };
+        DiePlan dealt = deal(settle_target(first, per_die, deal), false);
         // When the records are few and long compared with a workgroup's share (small layers), dealing whole
-        // records leaves the workgroups uneven; filling them one after the other is then the better plan.
+        // records and cutting the rest leaves the workgroups uneven; filling them one after the other may then
+        // be the better plan, or not cutting at all.
         const int64_t even = die_cost / per_die;
         if (dealt.makespan * 20 > even * 21) {
-            DiePlan filled = fill_in_order(q, per_die, even + kSegOverhead, budget);
+            DiePlan filled = fill(settle_target(first, per_die, fill), false);
             if (filled.makespan < dealt.makespan) dealt = std::move(filled);
+            const DiePlan whole = deal_whole(q, cost, per_die, true);
+            if (whole.makespan * 50 <= dealt.makespan * 51) dealt = deal_whole(q, cost, per_die, false);
         }
         for (int w = 0; w < per_die; ++w)
             for (difa_segment_t sg : dealt.lists[(size_t)w]) {
@@ -533,7 +616,7 @@ extern "C" difa_status_t difa_schedule_build(const difa_work_item_t* items, int3
                                              int32_t* wg_begin, int32_t* n_segs_out, difa_merge_item_t* merges,
                                              int32_t merge_capacity, int32_t* n_merges_out, int32_t* n_slots_out) {
     try {
-        return schedule_build(items, n_items, n_wg, n_xcd, segs, seg_capacity, wg_begin, n_segs_out, merges,
+        return schedule_build(items, n_items, n_wg, n_xcd, nullptr, segs, seg_capacity, wg_begin, n_segs_out, merges,
                               merge_capacity, n_merges_out, n_slots_out);
     } catch (const std::bad_alloc&) {
         return DIFA_ERR_ALLOC;
