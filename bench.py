@@ -105,8 +105,13 @@ class Layer:
 
     def wall_ms(self, steps, warmup):
         import torch
+        # W untimed steps.  The library learns the dies' speeds from finished launches and may then make the
+        # layer's schedule again (once or twice in a plan object's life); the pauses let that happen here,
+        # in the warm-up, as it would have long before the steady state of a real run.
         for i in range(warmup):
             self.step(i)
+            if i in (warmup - 3, warmup - 2):
+                torch.cuda.synchronize()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps):
@@ -310,6 +315,11 @@ def main():
     rse_avg = rse_ms / max(rse_calls, 1)
     head_rse = {"avg_kernel_ms": rse_avg, "bytes": rse_bytes, "GBps": rse_bytes / (rse_avg * 1e-3) * 1e-9 if rse_avg > 0 else None,
                 "frac_of_hbm_peak": rse_bytes / (rse_avg * 1e-3) * 1e-9 / PEAK_HBM_GBPS if rse_avg > 0 else None}
+    # what the plan object learnt about the dies' speeds from the workgroups' own run times, and how often
+    # it made this layer's schedule again because of it
+    speeds, speed_samples, retunes = B.difa_plan_die_speeds(lay.plan)
+    die_info = {"relative_speed": [round(x, 4) for x in speeds], "launches_averaged": speed_samples,
+                "schedules_made_again": retunes}
     lay.close()
 
     bm, bn = B.difa_tile_shape(wl.D)
@@ -363,6 +373,7 @@ def main():
         "launches_per_step": 1,
         "steady_state": steady,
         "device": B.difa_device_info(0),
+        "dies": die_info,
         "roofline": roofline,
         "head_rse": head_rse,
         "paper_context": PAPER_CONTEXT,

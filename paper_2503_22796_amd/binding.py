@@ -80,6 +80,8 @@ def _load():
                                   ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     L.difa_head_rse.restype = ctypes.c_int
     L.difa_head_rse.argtypes = [vp, vp, vp, i32, vp, vp]
+    L.difa_plan_die_speeds.restype = ctypes.c_int
+    L.difa_plan_die_speeds.argtypes = [vp, ctypes.POINTER(ctypes.c_double), i32, i32p, i32p, i32p]
     L.difa_plan_timing_read_head_rse.restype = ctypes.c_int
     L.difa_plan_timing_read_head_rse.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64), i32]
     L.difa_device_info.restype = ctypes.c_int
@@ -280,6 +282,16 @@ def difa_head_rse(plan, y_m, y_o, n_tokens, rse_out, stream=None):
                            ctypes.c_void_p(rse_out.data_ptr()), ctypes.c_void_p(s))
     if st != DIFA_OK:
         raise DifaError(st, difa_last_error(plan))
+
+
+def difa_plan_die_speeds(plan):
+    """(relative die speeds, launches averaged, schedules made again)"""
+    sp = (ctypes.c_double * 16)()
+    n, samples, retunes = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
+    st = lib.difa_plan_die_speeds(plan, sp, 16, ctypes.byref(n), ctypes.byref(samples), ctypes.byref(retunes))
+    if st != DIFA_OK:
+        raise DifaError(st, difa_last_error(plan))
+    return [float(sp[i]) for i in range(n.value)], samples.value, retunes.value
 
 
 def difa_plan_timing_read_head_rse(plan, reset=True):

@@ -6,11 +6,15 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
+#include <cmath>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
 
 #include "difa_internal.h"
+#include "difa_schedule.h"
 
 namespace {
 
@@ -18,12 +22,18 @@ constexpr int kSlots = 8;      // distinct (head plan, n_text, n_img) schedules 
 constexpr int kStagings = 16;  // pinned host buffers the schedules are uploaded from, used in turn
 constexpr int kXcd = 8;        // accelerator dies of an MI355X: workgroup p runs on die p % 8
 
+constexpr int kMaxDies = 16;
+constexpr int kRecent = 64;
+
 struct Slot {
     void* d_buf = nullptr;  // device: CACHE-head indices, then the schedule (or the debug path's work records)
     int32_t n_items = 0, n_copy = 0, n_merges = 0, n_slots = 0;
     size_t wg_off = 0, segs_off = 0, merges_off = 0, items_off = 0;  // byte offsets inside the buffer
     bool valid = false;
     uint64_t stamp = 0;
+    double speed_used[kMaxDies] = {};   // the die speeds the schedule was made for
+    int64_t die_span[kMaxDies] = {};    // predicted finishing time of each die, in the scheduler's cost units
+    int retunes = 0;                    // times the schedule was made again because the speeds had moved
 };
 
 struct Staging {
@@ -49,6 +59,17 @@ struct difa_plan {
     float* part_o = nullptr;       // device scratch for records cut into pieces: 2 * n_wg slots
     float* part_ml = nullptr;
     int32_t* ctl = nullptr;        // device: one ticket per cut record; zero between launches
+    // Die speeds (bf16 path).  Every workgroup of a launch reports how long it ran into pinned host memory;
+    // before the next schedule is made, the host turns the reports of the latest finished launch into
+    // relative speeds of the accelerator dies (predicted cost of a die's slowest workgroup / its measured
+    // time) and keeps a running average.  Nothing waits for a report: one that has not arrived is not used.
+    unsigned long long* h_times = nullptr;   // pinned, n_wg entries: launch tag << 32 | ticks
+    unsigned long long* d_times = nullptr;   // the same memory as the device addresses it
+    double die_speed[kMaxDies];              // mean 1
+    int speed_samples = 0, retunes = 0;
+    uint32_t launch_tag = 0, harvested_tag = 0;
+    struct Launch { uint32_t tag = 0; int64_t span[kMaxDies] = {}; };
+    Launch recent[kRecent];                  // the latest launches, by tag % kRecent: what each die was predicted to take
     double* rse_part = nullptr;    // device scratch of difa_head_rse: batch * heads * kRseChunks * 3 sums
     // Everything the object enqueues is kept in one order, whatever streams the calls name: the scratch
     // buffers, the counters and the schedule buffers are shared by all of them.  While the calls stay on
@@ -123,6 +144,8 @@ void free_buffers(difa_plan* p) {
         if (g.copied) (void)hipEventDestroy(g.copied);
         g = Staging();
     }
+    if (p->h_times) (void)hipHostFree(p->h_times);
+    p->h_times = p->d_times = nullptr;
     if (p->part_o) (void)hipFree(p->part_o);
     if (p->part_ml) (void)hipFree(p->part_ml);
     if (p->ctl) (void)hipFree(p->ctl);
@@ -132,6 +155,51 @@ void free_buffers(difa_plan* p) {
     p->ctl = nullptr;
     p->rse_part = nullptr;
     p->order_ev = nullptr;
+}
+
+constexpr int kMaxDevices = 64;
+struct DeviceSpeeds { double speed[kMaxDies]; int n_dies = 0; };
+DeviceSpeeds g_device_speeds[kMaxDevices];
+std::mutex g_speed_mutex;
+
+// Turns the run-time reports into die speeds when they are all from one launch (its workgroups have all ended
+// and no workgroup of a later launch has) and that launch is still remembered.
+void harvest_die_speeds(difa_plan* p) {
+    if (!p->h_times) return;
+    const int n_xcd = p->n_xcd;
+    unsigned long long ticks[kMaxDies] = {};
+    const volatile unsigned long long* t = p->h_times;
+    const uint32_t tag = (uint32_t)(t[0] >> 32);
+    if (tag == 0 || tag == p->harvested_tag) return;
+    const difa_plan::Launch& l = p->recent[tag % kRecent];
+    if (l.tag != tag) return;                                         // too long ago
+    for (int w = 0; w < p->n_wg; ++w) {
+        const unsigned long long v = t[w];
+        if ((uint32_t)(v >> 32) != tag) return;                       // two launches' reports side by side: not now
+        const unsigned long long ran = v & 0xffffffffull;
+        if (ran > ticks[w % n_xcd]) ticks[w % n_xcd] = ran;
+    }
+    p->harvested_tag = tag;
+    double rate[kMaxDies], mean = 0.0;
+    for (int x = 0; x < n_xcd; ++x) {
+        // (only launches that keep every die busy for a few dozen key-tile iterations say anything)
+        if (l.span[x] < 256 || ticks[x] < 1000) return;
+        rate[x] = (double)l.span[x] / (double)ticks[x];
+        mean += rate[x] / n_xcd;
+    }
+    for (int x = 0; x < n_xcd; ++x) {
+        double sp = rate[x] / mean;
+        sp = sp < 0.85 ? 0.85 : (sp > 1.15 ? 1.15 : sp);
+        p->die_speed[x] = p->speed_samples == 0 ? sp : 0.7 * p->die_speed[x] + 0.3 * sp;
+    }
+    ++p->speed_samples;
+    // (what one plan object has learnt is where the next one on this device starts)
+    if (p->desc.device >= 0 && p->desc.device < kMaxDevices) {
+        std::lock_guard<std::mutex> lock(g_speed_mutex);
+        DeviceSpeeds& g = g_device_speeds[p->desc.device];
+        for (int x = 0; x < n_xcd; ++x) g.speed[x] = p->die_speed[x];
+        g.n_dies = n_xcd;
+    }
 }
 
 // Puts what is about to be enqueued on `stream` behind everything this object enqueued before.
@@ -253,6 +321,7 @@ extern "C" difa_status_t difa_plan_create(const difa_plan_desc_t* desc, difa_pla
     difa_plan* p = new (std::nothrow) difa_plan();
     if (!p) return fail(nullptr, DIFA_ERR_ALLOC, "out of host memory");
     p->desc = *desc;
+    for (double& sp : p->die_speed) sp = 1.0;
     p->scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)desc->head_dim);
     difa_tile_shape(desc->head_dim, desc->dtype, &p->bm, &p->bn);
     const int64_t q_tiles = ((int64_t)desc->max_tokens + p->bm - 1) / p->bm;
@@ -290,6 +359,22 @@ extern "C" difa_status_t difa_plan_create(const difa_plan_desc_t* desc, difa_pla
         const size_t ctl_bytes = slots * sizeof(int32_t);
         if (e == hipSuccess) e = hipMalloc((void**)&p->ctl, ctl_bytes);
         if (e == hipSuccess) e = hipMemset(p->ctl, 0, ctl_bytes);      // (synchronous; the kernels leave them at zero)
+        if (e == hipSuccess && p->n_xcd > 1 && p->n_xcd <= kMaxDies) {
+            what = "allocating the run-time reports";
+            e = hipHostMalloc((void**)&p->h_times, (size_t)p->n_wg * sizeof(unsigned long long), hipHostMallocMapped);
+            if (e == hipSuccess) {
+                memset(p->h_times, 0, (size_t)p->n_wg * sizeof(unsigned long long));
+                e = hipHostGetDevicePointer((void**)&p->d_times, p->h_times, 0);
+            }
+            if (e == hipSuccess && desc->device >= 0 && desc->device < kMaxDevices) {
+                std::lock_guard<std::mutex> lock(g_speed_mutex);
+                const DeviceSpeeds& g = g_device_speeds[desc->device];
+                if (g.n_dies == p->n_xcd) {
+                    for (int x = 0; x < p->n_xcd; ++x) p->die_speed[x] = g.speed[x];
+                    p->speed_samples = 1;
+                }
+            }
+        }
     }
     if (e == hipSuccess) {
         what = "allocating work-list buffers";
@@ -371,6 +456,22 @@ extern "C" difa_status_t difa_plan_timing_read(difa_plan_t* p, double* attn_ms, 
     });
 }
 
+extern "C" difa_status_t difa_plan_die_speeds(difa_plan_t* p, double* speeds, int32_t capacity, int32_t* n_dies,
+                                              int32_t* samples, int32_t* retunes) {
+    if (!p) return DIFA_ERR_INVALID_ARG;
+    const int n = p->h_times ? p->n_xcd : 1;
+    if (n_dies) *n_dies = n;
+    if (samples) *samples = p->speed_samples;
+    if (retunes) *retunes = p->retunes;
+    if (speeds) {
+        if (capacity < n) return fail(p, DIFA_ERR_INVALID_ARG, "difa_plan_die_speeds: capacity below the number of dies");
+        harvest_die_speeds(p);
+        if (samples) *samples = p->speed_samples;
+        for (int x = 0; x < n; ++x) speeds[x] = p->h_times ? p->die_speed[x] : 1.0;
+    }
+    return DIFA_OK;
+}
+
 extern "C" difa_status_t difa_plan_timing_read_head_rse(difa_plan_t* p, double* rse_ms, int64_t* launches, int32_t reset) {
     return guarded(p, [&]() -> difa_status_t {
     if (!p) return DIFA_ERR_INVALID_ARG;
@@ -447,19 +548,34 @@ difa_status_t joint_attention_impl(difa_plan_t* p, const void* q, const void* k,
     }
     key[2 * H] = n_text;
     key[2 * H + 1] = n_img;
+    harvest_die_speeds(p);
+    const bool speeds_known = p->h_times && p->speed_samples >= 1;
     Slot* slot = nullptr;
+    int victim = -1;
     for (int s = 0; s < kSlots; ++s)
         if (p->slots[s].valid && memcmp(p->keys.data() + (size_t)s * key_len, key, key_len * sizeof(int32_t)) == 0) {
             slot = &p->slots[s];
+            // A schedule made for die speeds that have since moved by more than two hundredths is made again
+            // (twice at most, so that noise in the measurements cannot keep the host compiling).
+            if (speeds_known && slot->retunes < 2 && slot->n_items > 0) {
+                double off = 0.0;
+                for (int x = 0; x < p->n_xcd; ++x) off = std::max(off, std::fabs(p->die_speed[x] / slot->speed_used[x] - 1.0));
+                if (off > 0.02) { victim = s; slot = nullptr; }
+            }
             break;
         }
     if (!slot) {
-        int victim = 0;
-        for (int s = 0; s < kSlots; ++s) {
-            if (!p->slots[s].valid) { victim = s; break; }
-            if (p->slots[s].stamp < p->slots[victim].stamp) victim = s;
+        const bool retune = victim >= 0;
+        if (!retune) {
+            victim = 0;
+            for (int s = 0; s < kSlots; ++s) {
+                if (!p->slots[s].valid) { victim = s; break; }
+                if (p->slots[s].stamp < p->slots[victim].stamp) victim = s;
+            }
         }
         Slot* lru = &p->slots[victim];
+        lru->retunes = retune ? lru->retunes + 1 : 0;
+        if (retune) ++p->retunes;
         // The device buffer may still be read by launches enqueued earlier: the copy below goes on `stream`,
         // behind all of them.  The pinned buffer it is written into on the host may still be the source of a
         // copy issued kStagings distinct plans ago that the device has not reached yet: only then the host waits.
@@ -483,9 +599,12 @@ difa_status_t joint_attention_impl(difa_plan_t* p, const void* q, const void* k,
             lru->segs_off = (lru->wg_off + ((size_t)p->n_wg + 1) * sizeof(int32_t) + 63) / 64 * 64;
             const int32_t seg_cap = n_items + 2 * p->n_wg;
             lru->merges_off = (lru->segs_off + (size_t)seg_cap * sizeof(difa_segment_t) + 63) / 64 * 64;
-            st = difa_schedule_build(p->recs.data(), n_items, p->n_wg, p->n_xcd, (difa_segment_t*)(hb + lru->segs_off),
-                                     seg_cap, (int32_t*)(hb + lru->wg_off), &n_segs,
-                                     (difa_merge_item_t*)(hb + lru->merges_off), 2 * p->n_wg, &n_merges, &n_slots);
+            const bool dies = p->h_times != nullptr;
+            st = difa::schedule_for_dies(p->recs.data(), n_items, p->n_wg, p->n_xcd, dies && speeds_known ? p->die_speed : nullptr,
+                                         dies ? lru->die_span : nullptr, (difa_segment_t*)(hb + lru->segs_off),
+                                         seg_cap, (int32_t*)(hb + lru->wg_off), &n_segs,
+                                         (difa_merge_item_t*)(hb + lru->merges_off), 2 * p->n_wg, &n_merges, &n_slots);
+            for (int x = 0; x < kMaxDies; ++x) lru->speed_used[x] = dies && speeds_known && x < p->n_xcd ? p->die_speed[x] : 1.0;
             if (st != DIFA_OK) return fail(p, st, "scheduling the work list failed");
             used = lru->merges_off + (size_t)n_merges * sizeof(difa_merge_item_t);
         } else {
@@ -572,6 +691,14 @@ difa_status_t joint_attention_impl(difa_plan_t* p, const void* q, const void* k,
         a.scale = p->scale;
         if (fast) {
             a.tickets = p->ctl;
+            if (p->h_times && slot->n_items > 0) {
+                if (++p->launch_tag == 0) p->launch_tag = 1;
+                a.wg_times = p->d_times;
+                a.launch_tag = p->launch_tag;
+                difa_plan::Launch& l = p->recent[p->launch_tag % kRecent];
+                l.tag = p->launch_tag;
+                memcpy(l.span, slot->die_span, sizeof l.span);
+            }
             if (copies) {
                 const int vec_per_row = (int)(D * es / 16);                 // 8 or 16: a power of two
                 int shift = 0;

@@ -40,6 +40,10 @@ struct AttnArgs {
     int32_t tile_rot;    // key-tile position u of a record is tile (u + tile_rot) % n_kv_tiles
     int32_t n_kv_tiles;
     float scale;  // softmax scale (natural-log domain)
+    // bf16 kernel, optional: workgroup p leaves (launch_tag << 32 | its running time in ticks of the
+    // constant-rate 100 MHz counter) in wg_times[p] when it ends (host memory mapped into the device; NULL: off)
+    unsigned long long* wg_times;
+    uint32_t launch_tag;
 };
 
 struct CopyArgs {

@@ -128,7 +128,7 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
     auto vswz = [](int r) { return CPR == 16 ? 4 * (r & 3) : 2 * (r & 3); };
     __shared__ __attribute__((aligned(16))) __bf16 Ksm[NS * TILE];
     __shared__ __attribute__((aligned(16))) __bf16 Vsm[NS * TILE];
-    __shared__ int ctl_sm[1];                // a ticket, handed from thread 0 to the workgroup
+    __shared__ int ctl_sm[4];                // [0]: a ticket, handed from thread 0 to the workgroup; [2..3]: thread 0's start time
     // The arguments that only the rare paths use (merging a cut record, the cached-head copy) are read
     // from the kernel-argument block where they are needed: named through `a` they would be fetched at
     // kernel entry and held in scalar registers for the whole key loop, which has none to spare.
@@ -139,6 +139,9 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
     };
 
     const int tid = threadIdx.x, wave = tid >> 6;
+    // How long the workgroup runs is reported to the host, which learns from it how fast each accelerator
+    // die is going (their clocks differ by a few percent under load) and shares out later work accordingly.
+    // The start time waits in LDS (ctl_sm[2..3]): no register is held for it across the kernel.
     int l32, half;                                          // lane % 32, lane / 32 (set by lane_offsets below)
     const int N = a.n_tokens, n_text = a.n_text;
     // text tokens are [text_begin, text_begin + n_text), image tokens [img0, img1) (the text block sits
@@ -301,6 +304,13 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
         seg_next = a.segs[seg_first];
         lane_offsets();
         first_loads(seg_next, sbase);
+        // (the clock is read here, a few hundred clocks into the kernel, rather than on entry: at this point it
+        // costs no register that the key loop needs)
+        if (tid == 0) {
+            const unsigned long long t = wall_clock64();
+            ctl_sm[2] = (int)(unsigned)t;
+            ctl_sm[3] = (int)(unsigned)(t >> 32);
+        }
     }
     for (int seg_idx = seg_first; seg_idx < seg_end; ++seg_idx) {
     lane_offsets();
@@ -880,6 +890,18 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
     {
         const int copy_chunks = cold_args()->copy_chunks;
         for (; next_chunk < copy_chunks; next_chunk += (int)gridDim.x) copy_chunk(next_chunk);
+    }
+    if (tid == 0) {
+        const AttnArgs* ca = cold_args();
+        if (ca->wg_times) {
+            // (read through a pointer the compiler cannot trace back to the store, or it would carry the value
+            // in registers from one end of the kernel to the other)
+            const int* ts = ctl_sm;
+            asm volatile("" : "+v"(ts));
+            const unsigned long long t0 = (unsigned long long)(unsigned)ts[2] | ((unsigned long long)(unsigned)ts[3] << 32);
+            const unsigned long long ran = seg_first < seg_end ? wall_clock64() - t0 : 0;   // (no segments: no start time)
+            ca->wg_times[blockIdx.x] = ((unsigned long long)ca->launch_tag << 32) | (ran < 0xffffffffull ? ran : 0xffffffffull);
+        }
     }
 }
 

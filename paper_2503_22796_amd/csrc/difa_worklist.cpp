@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "difa.h"
+#include "difa_schedule.h"
 
 namespace {
 
@@ -496,8 +497,8 @@ DiePlan deal_whole(const std::vector<difa_work_item_t>& q, const std::vector<int
 }
 
 difa_status_t schedule_build(const difa_work_item_t* items, int32_t n_items, int32_t n_wg,
-                             int32_t n_xcd, const double* die_speed, difa_segment_t* segs, int32_t seg_capacity,
-                             int32_t* wg_begin, int32_t* n_segs_out, difa_merge_item_t* merges,
+                             int32_t n_xcd, const double* die_speed, int64_t* die_span, difa_segment_t* segs,
+                             int32_t seg_capacity, int32_t* wg_begin, int32_t* n_segs_out, difa_merge_item_t* merges,
                              int32_t merge_capacity, int32_t* n_merges_out, int32_t* n_slots_out) {
     if (n_items < 0 || (n_items > 0 && !items) || n_wg < 1 || n_xcd < 1 || n_wg % n_xcd != 0 || !wg_begin ||
         !n_segs_out || !n_merges_out || !n_slots_out || seg_capacity < 0 || merge_capacity < 0 ||
@@ -526,63 +527,97 @@ difa_status_t schedule_build(const difa_work_item_t* items, int32_t n_items, int
     std::stable_sort(spans.begin(), spans.end(), [](const HeadSpan& a, const HeadSpan& b) { return a.cost > b.cost; });
     int64_t total = 0;
     for (const HeadSpan& sp : spans) total += sp.cost;
-    std::vector<double> upto((size_t)n_xcd + 1, 0.0);      // cumulative share of the work that dies 0 .. x-1 take
-    {
-        double sum = 0.0;
-        for (int x = 0; x < n_xcd; ++x) sum += die_speed ? die_speed[x] : 1.0;
-        for (int x = 0; x < n_xcd; ++x) upto[(size_t)x + 1] = upto[(size_t)x] + (die_speed ? die_speed[x] : 1.0) / sum;
-        upto[(size_t)n_xcd] = 2.0;
-    }
-    std::vector<std::vector<difa_work_item_t>> die((size_t)n_xcd);
-    int64_t cum = 0;
-    int x_at = 0;
-    for (const HeadSpan& sp : spans)
-        for (size_t k = 0; k < sp.count; ++k) {
-            const difa_work_item_t& r = recs[sp.first + k];
-            const int64_t c = whole_cost(r);
-            const double mid = total > 0 ? (double)(2 * cum + c) / (double)(2 * total) : 0.0;
-            while (x_at < n_xcd - 1 && mid >= upto[(size_t)x_at + 1]) ++x_at;
-            die[(size_t)x_at].push_back(r);
-            cum += c;
-        }
-
     const int per_die = n_wg / n_xcd;
     const int slot_capacity = 2 * n_wg;
+    std::vector<double> speed((size_t)n_xcd, 1.0);         // relative speeds of the dies (their clocks differ under load)
+    if (die_speed)
+        for (int x = 0; x < n_xcd; ++x) speed[(size_t)x] = die_speed[x] > 0.5 && die_speed[x] < 2.0 ? die_speed[x] : 1.0;
+    std::vector<double> share(speed);                      // the part of the work each die is given, up to a common factor
+    std::vector<DiePlan> plans((size_t)n_xcd), first_plans;
+    double first_t_max = 0.0;
+    std::vector<int64_t> cost;
+    // Two rounds at most: the first hands out the work in proportion to the dies' speeds; where the plans that
+    // come out of it would finish more than three hundredths apart (a die whose records had to be cut carries the
+    // overhead of the cuts), the shares are corrected by that and the plans made again, and kept if they are better.
+    for (int round = 0; round < 2; ++round) {
+        std::vector<double> upto((size_t)n_xcd + 1, 0.0);  // cumulative share of the work that dies 0 .. x-1 take
+        {
+            double sum = 0.0;
+            for (int x = 0; x < n_xcd; ++x) sum += share[(size_t)x];
+            for (int x = 0; x < n_xcd; ++x) upto[(size_t)x + 1] = upto[(size_t)x] + share[(size_t)x] / sum;
+            upto[(size_t)n_xcd] = 2.0;
+        }
+        std::vector<std::vector<difa_work_item_t>> die((size_t)n_xcd);
+        int64_t cum = 0;
+        int x_at = 0;
+        for (const HeadSpan& sp : spans)
+            for (size_t k = 0; k < sp.count; ++k) {
+                const difa_work_item_t& r = recs[sp.first + k];
+                const int64_t c = whole_cost(r);
+                const double mid = total > 0 ? (double)(2 * cum + c) / (double)(2 * total) : 0.0;
+                while (x_at < n_xcd - 1 && mid >= upto[(size_t)x_at + 1]) ++x_at;
+                die[(size_t)x_at].push_back(r);
+                cum += c;
+            }
+        int slots_so_far = 0;
+        for (int x = 0; x < n_xcd; ++x) {
+            std::vector<difa_work_item_t>& q = die[(size_t)x];
+            // costliest records first (a query tile that holds text rows visits every key tile); the interior
+            // query tiles of a head cost the same and stay neighbours
+            {
+                std::vector<std::pair<int64_t, int>> key(q.size());
+                for (size_t i = 0; i < q.size(); ++i) key[i] = {-whole_cost(q[i]), (int)i};
+                std::sort(key.begin(), key.end());                   // (ties keep their order: the index decides)
+                std::vector<difa_work_item_t> sorted(q.size());
+                cost.resize(q.size());
+                for (size_t i = 0; i < q.size(); ++i) { sorted[i] = q[(size_t)key[i].second]; cost[i] = -key[i].first; }
+                q.swap(sorted);
+            }
+            int64_t die_cost = 0;
+            for (size_t i = 0; i < q.size(); ++i) die_cost += cost[i];
+            const int budget = slot_capacity - slots_so_far - 2 * per_die * (n_xcd - 1 - x);   // this die's share of the slots
+            // every workgroup is expected to take one piece
+            const int64_t first = (die_cost + (int64_t)per_die * kPieceExpected + per_die - 1) / per_die;
+            auto deal = [&](int64_t t, bool dry) { return deal_and_pour(q, cost, per_die, t, budget, dry); };
+            auto fill = [&](int64_t t, bool dry) { return fill_in_order(q, cost, per_die, t, budget, dry); };
+            DiePlan dealt = deal(settle_target(first, per_die, deal), false);
+            // When the records are few and long compared with a workgroup's share (small layers), dealing whole
+            // records and cutting the rest leaves the workgroups uneven; filling them one after the other may
+            // then be the better plan, or not cutting at all.
+            const int64_t even = die_cost / per_die;
+            if (dealt.makespan * 20 > even * 21) {
+                DiePlan filled = fill(settle_target(first, per_die, fill), false);
+                if (filled.makespan < dealt.makespan) dealt = std::move(filled);
+                const DiePlan whole = deal_whole(q, cost, per_die, true);
+                if (whole.makespan * 50 <= dealt.makespan * 51) dealt = deal_whole(q, cost, per_die, false);
+            }
+            slots_so_far += dealt.n_slots;
+            plans[(size_t)x] = std::move(dealt);
+        }
+        // predicted finishing times, in cost units of a die of speed 1
+        double t_min = 0.0, t_max = 0.0, t_sum = 0.0;
+        for (int x = 0; x < n_xcd; ++x) {
+            const double t = (double)plans[(size_t)x].makespan / speed[(size_t)x];
+            t_min = x == 0 ? t : std::min(t_min, t);
+            t_max = std::max(t_max, t);
+            t_sum += t;
+        }
+        if (round == 1) {
+            if (t_max >= first_t_max) plans.swap(first_plans);       // the correction did not help: keep the first plans
+            break;
+        }
+        if (t_sum <= 0.0 || t_min <= 0.0 || (t_max - t_min) * n_xcd <= 0.03 * t_sum) break;
+        for (int x = 0; x < n_xcd; ++x)
+            share[(size_t)x] *= (t_sum / n_xcd) / ((double)plans[(size_t)x].makespan / speed[(size_t)x]);
+        first_t_max = t_max;
+        first_plans = plans;
+    }
     std::vector<std::vector<difa_segment_t>> lists((size_t)n_wg);
     std::vector<difa_merge_item_t> merge_list;
-    std::vector<int64_t> cost;
     int n_slots = 0;
     for (int x = 0; x < n_xcd; ++x) {
-        std::vector<difa_work_item_t>& q = die[(size_t)x];
-        // costliest records first (a query tile that holds text rows visits every key tile); the interior
-        // query tiles of a head cost the same and stay neighbours
-        {
-            std::vector<std::pair<int64_t, int>> key(q.size());
-            for (size_t i = 0; i < q.size(); ++i) key[i] = {-whole_cost(q[i]), (int)i};
-            std::sort(key.begin(), key.end());                       // (ties keep their order: the index decides)
-            std::vector<difa_work_item_t> sorted(q.size());
-            cost.resize(q.size());
-            for (size_t i = 0; i < q.size(); ++i) { sorted[i] = q[(size_t)key[i].second]; cost[i] = -key[i].first; }
-            q.swap(sorted);
-        }
-        int64_t die_cost = 0;
-        for (size_t i = 0; i < q.size(); ++i) die_cost += cost[i];
-        const int budget = slot_capacity - n_slots - 2 * per_die * (n_xcd - 1 - x);   // this die's share of the slots
-        // every workgroup is expected to take one piece
-        const int64_t first = (die_cost + (int64_t)per_die * kPieceExpected + per_die - 1) / per_die;
-        auto deal = [&](int64_t t, bool dry) { return deal_and_pour(q, cost, per_die, t, budget, dry); };
-        auto fill = [&](int64_t t, bool dry) { return fill_in_order(q, cost, per_die, t, budget, dry); };
-        DiePlan dealt = deal(settle_target(first, per_die, deal), false);
-        // When the records are few and long compared with a workgroup's share (small layers), dealing whole
-        // records and cutting the rest leaves the workgroups uneven; filling them one after the other may then
-        // be the better plan, or not cutting at all.
-        const int64_t even = die_cost / per_die;
-        if (dealt.makespan * 20 > even * 21) {
-            DiePlan filled = fill(settle_target(first, per_die, fill), false);
-            if (filled.makespan < dealt.makespan) dealt = std::move(filled);
-            const DiePlan whole = deal_whole(q, cost, per_die, true);
-            if (whole.makespan * 50 <= dealt.makespan * 51) dealt = deal_whole(q, cost, per_die, false);
-        }
+        const DiePlan& dealt = plans[(size_t)x];
+        if (die_span) die_span[x] = dealt.makespan;
         for (int w = 0; w < per_die; ++w)
             for (difa_segment_t sg : dealt.lists[(size_t)w]) {
                 if (sg.part_slot >= 0) { sg.part_slot += n_slots; sg.first_slot += n_slots; sg.merge_idx += (int32_t)merge_list.size(); }
@@ -616,8 +651,23 @@ extern "C" difa_status_t difa_schedule_build(const difa_work_item_t* items, int3
                                              int32_t* wg_begin, int32_t* n_segs_out, difa_merge_item_t* merges,
                                              int32_t merge_capacity, int32_t* n_merges_out, int32_t* n_slots_out) {
     try {
-        return schedule_build(items, n_items, n_wg, n_xcd, nullptr, segs, seg_capacity, wg_begin, n_segs_out, merges,
-                              merge_capacity, n_merges_out, n_slots_out);
+        return schedule_build(items, n_items, n_wg, n_xcd, nullptr, nullptr, segs, seg_capacity, wg_begin, n_segs_out,
+                              merges, merge_capacity, n_merges_out, n_slots_out);
+    } catch (const std::bad_alloc&) {
+        return DIFA_ERR_ALLOC;
+    }
+}
+
+// The same for the library's own calls: with the dies' relative speeds as measured on earlier launches (NULL:
+// all alike), and returning each die's predicted finishing time in the scheduler's cost units.
+difa_status_t difa::schedule_for_dies(const difa_work_item_t* items, int32_t n_items, int32_t n_wg, int32_t n_xcd,
+                                      const double* die_speed, int64_t* die_span, difa_segment_t* segs,
+                                      int32_t seg_capacity, int32_t* wg_begin, int32_t* n_segs_out,
+                                      difa_merge_item_t* merges, int32_t merge_capacity, int32_t* n_merges_out,
+                                      int32_t* n_slots_out) {
+    try {
+        return schedule_build(items, n_items, n_wg, n_xcd, die_speed, die_span, segs, seg_capacity, wg_begin, n_segs_out,
+                              merges, merge_capacity, n_merges_out, n_slots_out);
     } catch (const std::bad_alloc&) {
         return DIFA_ERR_ALLOC;
     }

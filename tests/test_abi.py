@@ -86,6 +86,7 @@ def test_head_rse_with_null_plan_is_an_error_not_a_crash():
     from paper_2503_22796_amd import binding as B
     assert B.lib.difa_head_rse(None, None, None, 1, None, None) == B.DIFA_ERR_INVALID_ARG
     assert B.lib.difa_plan_timing_read_head_rse(None, None, None, 0) == B.DIFA_ERR_INVALID_ARG
+    assert B.lib.difa_plan_die_speeds(None, None, 0, None, None, None) == B.DIFA_ERR_INVALID_ARG
 
 
 def test_product_package_does_not_import_the_oracle():
