@@ -223,6 +223,52 @@ def test_schedule_of_the_2k_layers_is_balanced():
         assert len(merges) > 0           # the tail records are cut
 
 
+def _predicted_loads(items, segs, wg_begin, n_wg):
+    """Per-workgroup load under the measured cost model, written out again here (eighths of a plain key-tile
+    iteration: 8 per tile, 7 more on a tile that needs the element mask, 36 to start and finish a whole record,
+    72 for a piece of a cut record plus 40 per other piece for the one that folds, shared evenly)."""
+    by_key = {(int(r["bh"]), int(r["q_tile"])): r for r in items}
+    load = np.zeros(n_wg)
+    for w in range(n_wg):
+        for sg in segs[wg_begin[w]:wg_begin[w + 1]]:
+            r = by_key[(int(sg["bh"]), int(sg["q_tile"]))]
+            masked = 0
+            for p in range(int(sg["pos_begin"]), int(sg["pos_end"])):
+                if p < r["kv0_end"]:
+                    masked += p >= min(r["nm0_end"], r["kv0_end"])
+                else:
+                    t = r["kv1_begin"] + (p - r["kv0_end"])
+                    masked += not (r["nm1_begin"] <= t < r["nm1_end"])
+            n = int(sg["pos_end"] - sg["pos_begin"])
+            parts = int(sg["n_parts"])
+            load[w] += 8 * n + 7 * masked + (36 if sg["part_slot"] < 0 else 72 + 40 * (parts - 1) / parts)
+    return load
+
+
+def test_schedule_quality_on_the_named_layers():
+    """Every compute unit finishes together, as far as the cost model can tell, and a cut record has few pieces
+    (the workgroup that folds them reads every other piece's partial result at the very end of its work)."""
+    from paper_2503_22796_amd import workloads as W
+    for wl, bound in ((W.flux_2k_full(), 1.02), (W.flux_2k_mixed(), 1.04), (W.sd3_2k(), 1.05),
+                      (W.video_like(), 1.04)):
+        bm = 256
+        args = (wl.B, wl.H, wl.head_plan, wl.window, wl.n_text, wl.n_img, bm, 64)
+        items, segs, wg_begin, merges, n_slots = _schedule(args, 256, 8)
+        load = _predicted_loads(items, segs, wg_begin, 256)
+        assert load.max() <= bound * load.mean(), (wl.name, load.max() / load.mean())
+        assert max((int(m["n_parts"]) for m in merges), default=1) <= 3, wl.name
+
+
+def test_schedule_of_short_layers_does_not_cut_records_it_cannot_afford():
+    # a 1K layer has one or two records per compute unit, and a cut costs a sixth of such a record: few cuts
+    from paper_2503_22796_amd import workloads as W
+    wl = W.flux_1k()
+    args = (wl.B, wl.H, wl.head_plan, wl.window, wl.n_text, wl.n_img, 256, 64)
+    items, segs, wg_begin, merges, n_slots = _schedule(args, 256, 8)
+    _check_schedule(items, segs, wg_begin, merges, n_slots, 256, 8)
+    assert len(merges) <= len(items) // 8
+
+
 def test_schedule_rejects_bad_arguments():
     st, items, _ = B.difa_worklist_build(1, 1, [FULL], [0], 4, 60, 256, 64, 1)
     assert B.difa_schedule_build(items, 12, 8)[0] == B.DIFA_ERR_INVALID_ARG      # n_wg not a multiple of n_xcd
