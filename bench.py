@@ -106,11 +106,11 @@ class Layer:
     def wall_ms(self, steps, warmup):
         import torch
         # W untimed steps.  The library learns the dies' speeds from finished launches and may then make the
-        # layer's schedule again (once or twice in a plan object's life); the pauses let that happen here,
+        # layer's schedule again (it tries two versions and keeps the faster); the pauses let that happen here,
         # in the warm-up, as it would have long before the steady state of a real run.
         for i in range(warmup):
             self.step(i)
-            if i in (warmup - 3, warmup - 2):
+            if i >= warmup - 9:
                 torch.cuda.synchronize()
         torch.cuda.synchronize()
         t0 = time.perf_counter()

@@ -320,14 +320,16 @@ difa_status_t difa_plan_timing_read(difa_plan_t* plan, double* attn_ms, double* 
 difa_status_t difa_plan_timing_read_head_rse(difa_plan_t* plan, double* rse_ms, int64_t* launches, int32_t reset);
 /*
  * What the plan object has learnt about the accelerator dies.  Under load the dies of one GPU settle at
- * clocks a few percent apart; the bf16 kernel reports how long each workgroup ran, and the object shares
- * the work of later schedules out in proportion to the dies' speeds (a memoised schedule is made again,
- * twice at most, when the speeds have moved by more than two hundredths since it was made).  No call
- * waits for a report: a call uses what has arrived by then.
+ * clocks a few percent apart; the bf16 kernel reports how long each workgroup ran, the object averages the
+ * dies' relative speeds from the reports of finished launches, and a layer's schedule exists in two versions:
+ * dies alike, or work in proportion to the speeds.  The version made first runs until three launches of it
+ * have been timed, then the other one, then the faster of the two stays (so a memoised schedule is made
+ * again at most twice in its life).  No call waits for a report: a call uses what has arrived by then.
  *   speeds     HOST array of `capacity` doubles: receives the relative speeds (mean 1), one per die.
  *   n_dies     number of dies the scheduler distinguishes (1: the mechanism is off).
  *   samples    launches whose reports went into the running average (a new plan object starts from what
- *              earlier ones on the same device have learnt, counted as one); at 0 every die counts as 1.0.
+ *              earlier ones on the same device have learnt, counted as three); below three every die counts
+ *              as 1.0.
  *   retunes    memoised schedules made again so far.
  * Returns INVALID_ARG for a NULL plan or too small a capacity.  Lifecycle/diagnostic call: it matches no
  * passage of the paper.

@@ -31,9 +31,15 @@ struct Slot {
     size_t wg_off = 0, segs_off = 0, merges_off = 0, items_off = 0;  // byte offsets inside the buffer
     bool valid = false;
     uint64_t stamp = 0;
-    double speed_used[kMaxDies] = {};   // the die speeds the schedule was made for
     int64_t die_span[kMaxDies] = {};    // predicted finishing time of each die, in the scheduler's cost units
-    int retunes = 0;                    // times the schedule was made again because the speeds had moved
+    // The schedule exists in two versions: dies alike (0), or work in proportion to the measured die speeds (1).
+    // Which one is faster is measured, not assumed: the one made first runs until three launches of it have
+    // been timed, then the other one, then the faster of the two stays.
+    int version = 0;                    // the one in the buffer
+    int trial = 0;                      // 0: first version on trial, 1: second version on trial, 2: settled
+    uint32_t sched_id = 0;              // names this compilation (run-time reports are credited to it)
+    double ticks[2] = {0.0, 0.0};       // measured launch times per version, summed
+    int timed[2] = {0, 0};
 };
 
 struct Staging {
@@ -66,9 +72,10 @@ struct difa_plan {
     unsigned long long* h_times = nullptr;   // pinned, n_wg entries: launch tag << 32 | ticks
     unsigned long long* d_times = nullptr;   // the same memory as the device addresses it
     double die_speed[kMaxDies];              // mean 1
-    int speed_samples = 0, retunes = 0;
+    int speed_samples = 0, retunes = 0, reports_seen = 0;
     uint32_t launch_tag = 0, harvested_tag = 0;
-    struct Launch { uint32_t tag = 0; int64_t span[kMaxDies] = {}; };
+    struct Launch { uint32_t tag = 0; int64_t span[kMaxDies] = {}; int slot = -1; uint32_t sched_id = 0; };
+    uint32_t next_sched_id = 0;
     Launch recent[kRecent];                  // the latest launches, by tag % kRecent: what each die was predicted to take
     double* rse_part = nullptr;    // device scratch of difa_head_rse: batch * heads * kRseChunks * 3 sums
     // Everything the object enqueues is kept in one order, whatever streams the calls name: the scratch
@@ -180,6 +187,18 @@ void harvest_die_speeds(difa_plan* p) {
         if (ran > ticks[w % n_xcd]) ticks[w % n_xcd] = ran;
     }
     p->harvested_tag = tag;
+    if (l.slot >= 0 && l.slot < kSlots) {                             // the launch's own time, for its schedule's trial
+        Slot& sl = p->slots[l.slot];
+        unsigned long long longest = 0;
+        for (int x = 0; x < n_xcd; ++x) longest = std::max(longest, ticks[x]);
+        if (sl.valid && sl.sched_id == l.sched_id && sl.trial < 2 && longest > 0) {
+            if (p->reports_seen > 0) {                                // (the process's very first launch runs on a cold chip)
+                sl.ticks[sl.version] += (double)longest;
+                ++sl.timed[sl.version];
+            }
+        }
+    }
+    ++p->reports_seen;
     double rate[kMaxDies], mean = 0.0;
     for (int x = 0; x < n_xcd; ++x) {
         // (only launches that keep every die busy for a few dozen key-tile iterations say anything)
@@ -371,7 +390,7 @@ extern "C" difa_status_t difa_plan_create(const difa_plan_desc_t* desc, difa_pla
                 const DeviceSpeeds& g = g_device_speeds[desc->device];
                 if (g.n_dies == p->n_xcd) {
                     for (int x = 0; x < p->n_xcd; ++x) p->die_speed[x] = g.speed[x];
-                    p->speed_samples = 1;
+                    p->speed_samples = 3;                             // (counts as known)
                 }
             }
         }
@@ -549,18 +568,24 @@ difa_status_t joint_attention_impl(difa_plan_t* p, const void* q, const void* k,
     key[2 * H] = n_text;
     key[2 * H + 1] = n_img;
     harvest_die_speeds(p);
-    const bool speeds_known = p->h_times && p->speed_samples >= 1;
+    const bool speeds_known = p->h_times && p->speed_samples >= 3;
     Slot* slot = nullptr;
-    int victim = -1;
+    int victim = -1, want_version = -1;
     for (int s = 0; s < kSlots; ++s)
         if (p->slots[s].valid && memcmp(p->keys.data() + (size_t)s * key_len, key, key_len * sizeof(int32_t)) == 0) {
             slot = &p->slots[s];
-            // A schedule made for die speeds that have since moved by more than two hundredths is made again
-            // (twice at most, so that noise in the measurements cannot keep the host compiling).
-            if (speeds_known && slot->retunes < 2 && slot->n_items > 0) {
-                double off = 0.0;
-                for (int x = 0; x < p->n_xcd; ++x) off = std::max(off, std::fabs(p->die_speed[x] / slot->speed_used[x] - 1.0));
-                if (off > 0.02) { victim = s; slot = nullptr; }
+            // The trial of the schedule's two versions (see Slot): made again at most twice in its life.
+            if (p->h_times && slot->n_items > 0 && slot->trial < 2 && slot->timed[slot->version] >= 3) {
+                const int other = 1 - slot->version;
+                if (slot->trial == 0) {
+                    if (other == 0 || speeds_known) { want_version = other; slot->trial = 1; }
+                } else {
+                    const double mine = slot->ticks[slot->version] / slot->timed[slot->version];
+                    const double theirs = slot->timed[other] > 0 ? slot->ticks[other] / slot->timed[other] : 1e300;
+                    if (theirs < mine * 0.997) want_version = other;  // the earlier version was faster after all
+                    slot->trial = 2;
+                }
+                if (want_version >= 0) { victim = s; slot = nullptr; }
             }
             break;
         }
@@ -574,8 +599,16 @@ difa_status_t joint_attention_impl(difa_plan_t* p, const void* q, const void* k,
             }
         }
         Slot* lru = &p->slots[victim];
-        lru->retunes = retune ? lru->retunes + 1 : 0;
-        if (retune) ++p->retunes;
+        if (retune) {
+            ++p->retunes;
+            lru->version = want_version;
+        } else {
+            lru->version = speeds_known ? 1 : 0;
+            lru->trial = 0;
+            lru->ticks[0] = lru->ticks[1] = 0.0;
+            lru->timed[0] = lru->timed[1] = 0;
+        }
+        lru->sched_id = ++p->next_sched_id;
         // The device buffer may still be read by launches enqueued earlier: the copy below goes on `stream`,
         // behind all of them.  The pinned buffer it is written into on the host may still be the source of a
         // copy issued kStagings distinct plans ago that the device has not reached yet: only then the host waits.
@@ -600,11 +633,10 @@ difa_status_t joint_attention_impl(difa_plan_t* p, const void* q, const void* k,
             const int32_t seg_cap = n_items + 2 * p->n_wg;
             lru->merges_off = (lru->segs_off + (size_t)seg_cap * sizeof(difa_segment_t) + 63) / 64 * 64;
             const bool dies = p->h_times != nullptr;
-            st = difa::schedule_for_dies(p->recs.data(), n_items, p->n_wg, p->n_xcd, dies && speeds_known ? p->die_speed : nullptr,
+            st = difa::schedule_for_dies(p->recs.data(), n_items, p->n_wg, p->n_xcd, dies && lru->version == 1 ? p->die_speed : nullptr,
                                          dies ? lru->die_span : nullptr, (difa_segment_t*)(hb + lru->segs_off),
                                          seg_cap, (int32_t*)(hb + lru->wg_off), &n_segs,
                                          (difa_merge_item_t*)(hb + lru->merges_off), 2 * p->n_wg, &n_merges, &n_slots);
-            for (int x = 0; x < kMaxDies; ++x) lru->speed_used[x] = dies && speeds_known && x < p->n_xcd ? p->die_speed[x] : 1.0;
             if (st != DIFA_OK) return fail(p, st, "scheduling the work list failed");
             used = lru->merges_off + (size_t)n_merges * sizeof(difa_merge_item_t);
         } else {
@@ -697,6 +729,8 @@ difa_status_t joint_attention_impl(difa_plan_t* p, const void* q, const void* k,
                 a.launch_tag = p->launch_tag;
                 difa_plan::Launch& l = p->recent[p->launch_tag % kRecent];
                 l.tag = p->launch_tag;
+                l.slot = (int)(slot - p->slots);
+                l.sched_id = slot->sched_id;
                 memcpy(l.span, slot->die_span, sizeof l.span);
             }
             if (copies) {

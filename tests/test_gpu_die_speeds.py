@@ -27,7 +27,7 @@ def test_die_speeds_are_learnt_and_the_retuned_schedule_computes_the_same_layer(
         torch.cuda.synchronize()
         out = torch.empty_like(qd)
         seen_retune = retunes
-        for _ in range(12):                       # a report is picked up by the call after the launch has ended
+        for _ in range(14):                       # a report is picked up by the call after the launch has ended
             out.fill_(float("nan"))
             B.difa_joint_attention(plan, qd, kd, vd, out, cd, wl.head_plan, wl.n_text, wl.n_img, wl.window)
             torch.cuda.synchronize()
