@@ -39,8 +39,8 @@ __device__ __forceinline__ float halves_sum(float x) {
 // wavefronts, two per SIMD) and stays resident: it walks the list of segments the host scheduler gave
 // it.  A segment is a 256-row query tile of one (batch, head) together with a
 // run of that record's key/value tiles (the whole run for most records; a few records are cut so
-// that every workgroup ends at the same time, and their pieces leave fp32 partial results that
-// merge_parts_kernel combines).  Wavefront w owns rows 32*QB*w .. 32*QB*(w+1)-1 as QB 32-row blocks.
+// that every workgroup ends at the same time, and their pieces leave fp32 partial results that the
+// piece finishing last folds into its own).  Wavefront w owns rows 32*QB*w .. 32*QB*(w+1)-1 as QB 32-row blocks.
 // Key/value tiles of 64 keys are written into 4-stage LDS rings by the buffer-load-to-LDS DMA, K three
 // tiles and V two tiles ahead of their use, in the order the work record lists them (text tiles,
 // then the band tiles), so a tile with no allowed pair is never loaded (Sec. 3.1 / 3.3:
