@@ -310,8 +310,9 @@ difa_status_t difa_plan_solve(const double* influence, const double* latency, do
 /* ------------------------------------------------------------------ measurement hooks
  * With timing enabled the library brackets its kernel launches with HIP events on the caller's
  * stream; difa_plan_timing_read waits for the last bracket and returns the accumulated kernel
- * milliseconds and launch count since the last reset.  attn_ms: the layer kernel (on the bf16 path it
- * holds the cached-head copy as well); copy_ms: the separate copy kernel of the fp32 debug path.
+ * milliseconds and launch count since the last reset.  attn_ms: the call's layer kernel (on the bf16 path it
+ * holds the cached-head copy as well; a bf16 layer with every head cached is one launch of the copy kernel,
+ * counted here); copy_ms: the separate copy kernel of the fp32 debug path.
  */
 difa_status_t difa_plan_timing_enable(difa_plan_t* plan, int32_t enable);
 difa_status_t difa_plan_timing_read(difa_plan_t* plan, double* attn_ms, double* copy_ms,

@@ -669,8 +669,11 @@ difa_status_t joint_attention_impl(difa_plan_t* p, const void* q, const void* k,
     const bool fast = p->desc.dtype == DIFA_DTYPE_BF16;
     const bool copies = slot->n_copy > 0 && cache != out;   // cached heads (Sec. 3.2): out[b, h] = cache[b, h]
 
-    // ---- fp32 debug path: cached heads by a copy kernel of their own
-    if (!fast && copies) {
+    // ---- cached heads by a copy kernel of their own: on the fp32 debug path, and for a bf16 layer that computes no
+    // head at all (the copy kernel fills the chip with many small workgroups and moves a fifth more bytes per second
+    // than the layer kernel's one workgroup per compute unit; it is then the call's one launch)
+    const bool copy_only = fast && copies && slot->n_items == 0;
+    if (copies && (!fast || copy_only)) {
         difa::CopyArgs c{};
         c.src = cache;
         c.dst = out;
@@ -679,7 +682,7 @@ difa_status_t joint_attention_impl(difa_plan_t* p, const void* q, const void* k,
         c.batch = B; c.n_copy = slot->n_copy; c.n_tokens = N;
         c.vec_per_row = (int32_t)(D * es / 16);
         TimingPair tp{};
-        if (p->timing && (e = timing_begin(p, stream, 1, &tp)) != hipSuccess)
+        if (p->timing && (e = timing_begin(p, stream, copy_only ? 0 : 1, &tp)) != hipSuccess)
             return fail(p, DIFA_ERR_HIP, hip_msg("hipEventRecord", e));
         e = difa::launch_cache_copy(c, stream);
         if (p->timing) { (void)hipEventRecord(tp.stop, stream); p->pending.push_back(tp); }
@@ -687,7 +690,7 @@ difa_status_t joint_attention_impl(difa_plan_t* p, const void* q, const void* k,
     }
 
     // ---- one launch: the computed heads and, on the bf16 path, the cached heads as well
-    if (slot->n_items > 0 || (fast && copies)) {
+    if (slot->n_items > 0) {
         const char* db = (const char*)slot->d_buf;
         difa::AttnArgs a{};
         a.q = q; a.k = k; a.v = v; a.out = out;
