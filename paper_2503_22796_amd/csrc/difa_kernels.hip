@@ -92,6 +92,8 @@ __device__ __forceinline__ void mfma_s_acc(floatx16& d, const bf16x8& k, const b
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(k), "a"(q));
 }
 __device__ __forceinline__ void mfma_results_visible() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
+// (the same wait, tied to the registers it is for: no read of them can be moved ahead of it)
+__device__ __forceinline__ void mfma_results_visible(floatx16& d) { asm volatile("s_nop 15\n\ts_nop 15" : "+v"(d) :: "memory"); }
 
 // Cache-policy operand of the buffer load/store builtins: device scope ("sc1").
 constexpr int kDeviceCoherent = 16;
@@ -400,54 +402,56 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
     const int row_last = row_first + RW - 1 < N - 1 ? row_first + RW - 1 : N - 1;
     auto mask_block = [&](int j0, floatx16 (&s)[QB]) {
         const bool plain = j0 >= img0 && j0 + 31 < img1 && row_first >= img0 && row_last < img1 && it.window >= 0;
-        if (plain) {
-            // image rows, image keys, no tail: row i allows keys [i - w, i + w]
-            const bool low = row_last - it.window > j0;                    // some row's band starts after j0
-            const bool high = row_first + it.window < j0 + 31;             // some row's band ends before the block does
-            if (!low && !high) return;
-            // Register r of a lane holds the key at offset 8*(r/4) + r%4 (+ 4*half) of the block, increasing
-            // with r, so the keys below the band's start are the lane's first k registers and the keys beyond
-            // its end the last ones.  The count k comes from the lane's edge with a handful of integer
-            // instructions; bit r of `gone` says that register r is to be replaced, and each score then costs a
-            // signed one-bit extract (all ones or zero) and a bit-select between the score and -inf.  No
-            // compare writes a lane mask that the next instruction would have to wait for (a compare and a
-            // select that reads its result cost 20 clocks a pair on this chip, four ordinary instructions 16).
-            auto below = [](int e) {                                        // registers whose key offset is < e
-                const int ec = e < 0 ? 0 : (e > 32 ? 32 : e);
-                const int rem = ec & 7;
-                return 4 * (ec >> 3) + (rem < 4 ? rem : 4);
-            };
-            const unsigned ninf = 0xff800000u;
+        // image rows, image keys, no tail: row i allows keys [i - w, i + w]
+        const bool low = row_last - it.window > j0;                        // some row's band starts after j0
+        const bool high = row_first + it.window < j0 + 31;                 // some row's band ends before the block does
+        if (plain && !low && !high) return;
+        const unsigned ninf = 0xff800000u;
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                unsigned gone = 0;
+        for (int qb = 0; qb < QB; ++qb) {
+            // bit r of `gone` says that register r holds the score of a forbidden key
+            unsigned gone = 0;
+            if (plain) {
+                // Register r of a lane holds the key at offset 8*(r/4) + r%4 (+ 4*half) of the block, increasing
+                // with r, so the keys below the band's start are the lane's first k registers and the keys beyond
+                // its end the last ones.  The count k comes from the lane's edge with a handful of integer
+                // instructions.
+                auto below = [](int e) {                                    // registers whose key offset is < e
+                    const int ec = e < 0 ? 0 : (e > 32 ? 32 : e);
+                    const int rem = ec & 7;
+                    return 4 * (ec >> 3) + (rem < 4 ? rem : 4);
+                };
                 if (low) gone = (1u << below(rs[qb].lo - j0 - 4 * half)) - 1u;
                 if (high) gone |= ~((1u << below(rs[qb].lo + (int)rs[qb].span - j0 - 4 * half + 1)) - 1u);
-                // (one statement for the block's sixteen scores, written out so that the compiler neither turns
-                // the bit-select back into a compare and a select nor pads every score with a wait state)
-                float x[16];
+            } else {
+                // text keys or rows, or the tail of the sequence, in the block: one unsigned range test per segment and key
 #pragma unroll
-                for (int r = 0; r < 16; ++r) x[r] = s[qb][r];
-                unsigned t0, t1;
-                asm volatile("v_bfe_i32 %16, %18, 0, 1\n\tv_bfe_i32 %17, %18, 1, 1\n\tv_bfi_b32 %0, %16, %19, %0\n\tv_bfi_b32 %1, %17, %19, %1\n\tv_bfe_i32 %16, %18, 2, 1\n\tv_bfe_i32 %17, %18, 3, 1\n\tv_bfi_b32 %2, %16, %19, %2\n\tv_bfi_b32 %3, %17, %19, %3\n\tv_bfe_i32 %16, %18, 4, 1\n\tv_bfe_i32 %17, %18, 5, 1\n\tv_bfi_b32 %4, %16, %19, %4\n\tv_bfi_b32 %5, %17, %19, %5\n\tv_bfe_i32 %16, %18, 6, 1\n\tv_bfe_i32 %17, %18, 7, 1\n\tv_bfi_b32 %6, %16, %19, %6\n\tv_bfi_b32 %7, %17, %19, %7\n\tv_bfe_i32 %16, %18, 8, 1\n\tv_bfe_i32 %17, %18, 9, 1\n\tv_bfi_b32 %8, %16, %19, %8\n\tv_bfi_b32 %9, %17, %19, %9\n\tv_bfe_i32 %16, %18, 10, 1\n\tv_bfe_i32 %17, %18, 11, 1\n\tv_bfi_b32 %10, %16, %19, %10\n\tv_bfi_b32 %11, %17, %19, %11\n\tv_bfe_i32 %16, %18, 12, 1\n\tv_bfe_i32 %17, %18, 13, 1\n\tv_bfi_b32 %12, %16, %19, %12\n\tv_bfi_b32 %13, %17, %19, %13\n\tv_bfe_i32 %16, %18, 14, 1\n\tv_bfe_i32 %17, %18, 15, 1\n\tv_bfi_b32 %14, %16, %19, %14\n\tv_bfi_b32 %15, %17, %19, %15"
-                             : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]),
-                               "+v"(x[8]), "+v"(x[9]), "+v"(x[10]), "+v"(x[11]), "+v"(x[12]), "+v"(x[13]), "+v"(x[14]), "+v"(x[15]),
-                               "=&v"(t0), "=&v"(t1)
-                             : "v"(gone), "v"(ninf));
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s[qb][r] = x[r];
+                for (int r = 0; r < 16; ++r) {
+                    const int j = j0 + 8 * (r >> 2) + 4 * half + (r & 3);
+                    const bool ok = ((unsigned)(j - text_begin) < (unsigned)n_text) | ((unsigned)(j - rs[qb].lo) <= rs[qb].span);
+                    gone |= ok ? 0u : 1u << r;
+                }
             }
-            return;
+            // Each score then costs a signed one-bit extract (all ones or zero) and a bit-select between the score
+            // and -inf, in place.  No compare writes a lane mask that the next instruction would have to wait for
+            // (a compare and a select that reads its result cost 20 clocks a pair on this chip, four ordinary
+            // instructions 16), and the sixteen registers are not rebuilt elsewhere (a select per score into a
+            // fresh set of registers makes the compiler copy all sixteen over and back on every path through
+            // here, the one that changes nothing included).
+            // (one statement for the block's sixteen scores, written out so that the compiler neither turns
+            // the bit-select back into a compare and a select nor pads every score with a wait state)
+            float x[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) x[r] = s[qb][r];
+            unsigned t0, t1;
+            asm volatile("v_bfe_i32 %16, %18, 0, 1\n\tv_bfe_i32 %17, %18, 1, 1\n\tv_bfi_b32 %0, %16, %19, %0\n\tv_bfi_b32 %1, %17, %19, %1\n\tv_bfe_i32 %16, %18, 2, 1\n\tv_bfe_i32 %17, %18, 3, 1\n\tv_bfi_b32 %2, %16, %19, %2\n\tv_bfi_b32 %3, %17, %19, %3\n\tv_bfe_i32 %16, %18, 4, 1\n\tv_bfe_i32 %17, %18, 5, 1\n\tv_bfi_b32 %4, %16, %19, %4\n\tv_bfi_b32 %5, %17, %19, %5\n\tv_bfe_i32 %16, %18, 6, 1\n\tv_bfe_i32 %17, %18, 7, 1\n\tv_bfi_b32 %6, %16, %19, %6\n\tv_bfi_b32 %7, %17, %19, %7\n\tv_bfe_i32 %16, %18, 8, 1\n\tv_bfe_i32 %17, %18, 9, 1\n\tv_bfi_b32 %8, %16, %19, %8\n\tv_bfi_b32 %9, %17, %19, %9\n\tv_bfe_i32 %16, %18, 10, 1\n\tv_bfe_i32 %17, %18, 11, 1\n\tv_bfi_b32 %10, %16, %19, %10\n\tv_bfi_b32 %11, %17, %19, %11\n\tv_bfe_i32 %16, %18, 12, 1\n\tv_bfe_i32 %17, %18, 13, 1\n\tv_bfi_b32 %12, %16, %19, %12\n\tv_bfi_b32 %13, %17, %19, %13\n\tv_bfe_i32 %16, %18, 14, 1\n\tv_bfe_i32 %17, %18, 15, 1\n\tv_bfi_b32 %14, %16, %19, %14\n\tv_bfi_b32 %15, %17, %19, %15"
+                         : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]),
+                           "+v"(x[8]), "+v"(x[9]), "+v"(x[10]), "+v"(x[11]), "+v"(x[12]), "+v"(x[13]), "+v"(x[14]), "+v"(x[15]),
+                           "=&v"(t0), "=&v"(t1)
+                         : "v"(gone), "v"(ninf));
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[qb][r] = x[r];
         }
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int j = j0 + 8 * (r >> 2) + 4 * half + (r & 3);
-                // branch-free on purpose: one unsigned range test per segment
-                const bool ok = ((unsigned)(j - text_begin) < (unsigned)n_text) | ((unsigned)(j - rs[qb].lo) <= rs[qb].span);
-                s[qb][r] = ok ? s[qb][r] : -INFINITY;
-            }
     };
     // ---- softmax of one 32-key block, cut into 16 pieces of six VALU instructions, one per slot, each
     // split in two halves that sit behind the slot's two MFMAs (a wavefront issues in order:
@@ -632,7 +636,8 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_bf16_kernel(AttnArgs a) {
         for (int qb = 0; qb < QB; ++qb) rs[qb].l += lb[qb];
         // block number blk_nxt = 2*position + jb; its first key is only needed on this rare path
         if (__builtin_expect(mask_nxt, 0)) {
-            mfma_results_visible();
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) mfma_results_visible(s_nxt[qb]);
             mask_block(tile_of(blk_nxt >> 1) * kBN + 32 * (blk_nxt & 1), s_nxt);
         }
     };
